@@ -1,0 +1,154 @@
+/*
+ * libwkv -- the per-token decode step of WeightedKV on one AMD MI355X (gfx950).
+ *
+ * WeightedKV (arXiv 2503.01330) keeps a key/value cache of fixed size m during
+ * autoregressive decoding.  For every (sequence, head) pair -- a "unit"; the
+ * paper drops batch and head dimensions "for simplicity" (Section III-A), so
+ * units never interact -- one generated token does the following:
+ *
+ *   1. K_t = [K_{t-1}, k_t],  V_t = [V_{t-1}, v_t]                (Section III-A)
+ *   2. A_t = softmax(q_t^T K_t / sqrt(d)),  o_t = A_t^T V_t        (Sections III-A, III-B)
+ *   3. a = [a, 0] + A_t,  n = [n, 0] + 1                           (Algorithm 1)
+ *   4. if the cache now holds more than m entries:                 (Algorithm 1, Section IV)
+ *        abar = a / n
+ *        j    = arg-min of abar over the entries that are not protected
+ *        V[j+1] <- (abar[j] V[j] + abar[j+1] V[j+1]) / (abar[j] + abar[j+1])
+ *        remove K[j], V[j], a[j], n[j]
+ *
+ * "j+1" is the right-hand neighbour in token order.  Protected entries are the
+ * `recent_window` newest tokens (Algorithm 1 protects exactly the newest one,
+ * recent_window = 1; Section V-A keeps a recent region and 4 initial tokens)
+ * and, optionally, the first `n_sink` tokens.  Ties in the arg-min go to the
+ * oldest token.  The survivor keeps its own key, score sum and count.
+ *
+ * Everything above runs in hand-written HIP kernels; this header is the whole
+ * boundary.  All functions are thread-compatible (one handle must not be used
+ * from two threads at once), never throw, never abort, and return 0 or a
+ * negative WKV_E* code; wkv_last_error() gives the calling thread's message.
+ */
+#ifndef WKV_H
+#define WKV_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* storage / arithmetic-input types of q, k, v, out and of the K/V cache */
+#define WKV_FP32 0
+#define WKV_FP16 1
+#define WKV_BF16 2
+
+/* return codes */
+#define WKV_OK      0
+#define WKV_EINVAL -1   /* bad argument (null pointer, out-of-range value, misaligned buffer) */
+#define WKV_ENOMEM -2   /* device or host allocation failed */
+#define WKV_EHIP   -3   /* a HIP runtime call failed (no GPU, launch failure, ...) */
+#define WKV_ESIZE  -4   /* a size exceeds what this build supports, or a readback buffer is too small */
+
+/* limits of this build */
+#define WKV_MAX_BUDGET 4095   /* slots per unit, bounded by the LDS staging of one score row */
+
+/* which entries may be ranked / how the victim's value is treated (wkv_options) */
+#define WKV_SCORE_AVERAGE    0   /* abar = a / n: WeightedKV (Algorithm 1)                         */
+#define WKV_SCORE_CUMULATIVE 1   /* a: the cumulative-score rule the paper cites as H2O (Section II) */
+#define WKV_SCORE_LAST       2   /* the current step's attention weight: the rule cited as TOVA     */
+#define WKV_MERGE_CONVEX     0   /* fold V[j] into its right neighbour (Algorithm 1)                */
+#define WKV_MERGE_NONE       1   /* drop V[j] too: the "Eviction" ablation of Section V-B           */
+
+typedef struct wkv_handle wkv_handle;
+
+/* Every field is plain int so the struct can be filled from any language.
+ * Zero in an optional field means "default". */
+typedef struct wkv_options {
+    int batch, heads, head_dim;  /* units = batch*heads; head_dim in {64,128,256} (fp32: {64,128}) */
+    int budget;                  /* m, 1..WKV_MAX_BUDGET: slots kept after every step             */
+    int recent_window;           /* R, 1..budget: newest R tokens are never evicted               */
+    int dtype;                   /* WKV_FP32 / WKV_FP16 / WKV_BF16                                */
+    int n_sink;                  /* optional: first n_sink tokens are never evicted; n_sink+R <= m */
+    int score_mode;              /* optional: WKV_SCORE_*; non-average modes require WKV_MERGE_NONE */
+    int merge_mode;              /* optional: WKV_MERGE_*                                          */
+    int log_capacity;            /* optional: steps of eviction log kept (ring), default 1024      */
+    int threads;                 /* optional: workgroup size 256/512/1024, default chosen by units */
+    int reserved[5];             /* must be zero                                                   */
+} wkv_options;
+
+/*
+ * Create an empty cache (K_0, V_0 empty: Section III-A; a, n empty: Algorithm 1)
+ * for batch*heads units on the current HIP device.  The library allocates and
+ * owns the device memory: per unit (budget+1) rows of K and V in `dtype`, one
+ * fp64 score sum, one int32 original position and one int32 merge count per
+ * slot, plus the eviction log.  The softmax scale is 1/sqrt(head_dim).
+ * *h is written only on success.
+ */
+int wkv_create(wkv_handle** h, int batch, int heads, int head_dim,
+               int budget, int recent_window, int dtype);
+
+/* Same, with the optional knobs of wkv_options. */
+int wkv_create_ex(wkv_handle** h, const wkv_options* opt);
+
+/*
+ * One decode step (steps 1-4 above) for every unit.
+ *   q, k_new, v_new : DEVICE pointers, contiguous [batch, heads, head_dim] in
+ *                     the handle's dtype, 16-byte aligned, read only.
+ *   out             : DEVICE pointer, same shape and dtype, receives o_t.
+ *                     o_t is computed over the cache *including* the new token
+ *                     and *before* compression (Algorithm 1 obtains A_t ahead
+ *                     of its capacity test).
+ *   stream          : a hipStream_t (NULL = the default stream).
+ * Asynchronous: returns after enqueueing.  The caller owns the four buffers and
+ * must keep them valid until the stream reaches this step; the cache belongs to
+ * the handle.  After the step completes the cache holds min(tokens, budget)
+ * slots per unit.  Arguments are checked on the host before anything is
+ * launched; on error nothing is enqueued and the cache is unchanged.
+ */
+int wkv_step(wkv_handle* h, const void* q, const void* k_new, const void* v_new,
+             void* out, void* stream);
+
+/* what wkv_state reads back */
+#define WKV_STEP       0  /* int64[1]            tokens processed so far                             */
+#define WKV_LEN        1  /* int32[1]            live slots per unit = min(tokens, budget)           */
+#define WKV_K          2  /* dtype[units,len,d]  retained keys                                       */
+#define WKV_V          3  /* dtype[units,len,d]  (merged) values                                     */
+#define WKV_SCORE_SUM  4  /* double[units,len]   a: accumulated attention weight                     */
+#define WKV_COUNT      5  /* int32[units,len]    n: steps attended = tokens - pos                    */
+#define WKV_POS        6  /* int32[units,len]    0-based index of the token whose key is retained    */
+#define WKV_NMERGED    7  /* int32[units,len]    raw values folded into the slot                     */
+#define WKV_EVICT_POS  8  /* int32[n,units]      evicted token index per step, -1 if none            */
+#define WKV_EVICT_SLOT 9  /* int32[n,units]      its rank in token order among the len+1 slots, -1   */
+#define WKV_STATUS     10 /* int32[2]            {merges with zero denominator, non-finite scores}   */
+
+/*
+ * Synchronous readback into HOST memory (waits for all enqueued steps).  Slot
+ * arrays come back in token order (ascending WKV_POS), whatever the order in
+ * device memory.  For the two eviction logs, n = bytes / (4*units) most recent
+ * steps are returned, oldest first; n must not exceed min(tokens, log_capacity).
+ * For everything else `bytes` must be at least the size listed above
+ * (WKV_ESIZE otherwise; nothing is written then).
+ */
+int wkv_state(wkv_handle* h, int what, void* host_dst, size_t bytes);
+
+/* Free the cache.  Waits for enqueued work.  NULL is accepted. */
+int wkv_destroy(wkv_handle* h);
+
+/* Message of the last failing call on this thread ("" if none).  Never NULL. */
+const char* wkv_last_error(void);
+
+/* Device bytes a handle with these options allocates (0 if the options are invalid).
+ * Host-only arithmetic: usable without a GPU. */
+size_t wkv_workspace_bytes(const wkv_options* opt);
+
+/* Algorithmic HBM bytes one wkv_step moves in steady state (cache full): per
+ * unit (budget+1) K rows and V rows read, score sum read+written, position
+ * read, q/k_new/v_new read, out written, the new K/V rows written, two V rows
+ * read and one written by the merge.  Host-only arithmetic. */
+size_t wkv_step_bytes(const wkv_options* opt);
+
+int wkv_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* WKV_H */

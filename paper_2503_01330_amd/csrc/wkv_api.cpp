@@ -1,0 +1,313 @@
+// Host side of libwkv: handle management, argument checking, state readback.
+// The arithmetic of the method lives in wkv_step.hip; nothing here computes
+// attention, scores or merges.  See include/wkv.h for the contract.
+#include "../../include/wkv.h"
+#include "wkv_internal.h"
+
+#include <algorithm>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <numeric>
+#include <string>
+#include <vector>
+
+namespace {
+
+thread_local std::string g_err;
+
+int fail(int code, const char* fmt, ...)
+{
+    char buf[512];
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(buf, sizeof buf, fmt, ap);
+    va_end(ap);
+    g_err = buf;
+    return code;
+}
+
+int dtype_bytes(int dtype) { return dtype == WKV_FP32 ? 4 : 2; }
+
+constexpr size_t LDS_LIMIT = 64 * 1024;
+
+// Returns 0 and fills *threads, or a negative code with the reason in g_err.
+int validate(const wkv_options& o, int* threads)
+{
+    if (o.batch <= 0 || o.heads <= 0) return fail(WKV_EINVAL, "batch and heads must be positive");
+    if ((long long)o.batch * o.heads > (1 << 24)) return fail(WKV_ESIZE, "batch*heads exceeds 2^24 units");
+    if (o.dtype != WKV_FP32 && o.dtype != WKV_FP16 && o.dtype != WKV_BF16)
+        return fail(WKV_EINVAL, "dtype must be WKV_FP32, WKV_FP16 or WKV_BF16");
+    const bool d_ok = o.head_dim == 64 || o.head_dim == 128 || (o.head_dim == 256 && o.dtype != WKV_FP32);
+    if (!d_ok) return fail(WKV_EINVAL, "head_dim %d unsupported for this dtype (64, 128; 256 for 16-bit)", o.head_dim);
+    if (o.budget < 1) return fail(WKV_EINVAL, "budget must be at least 1");
+    if (o.budget > WKV_MAX_BUDGET) return fail(WKV_ESIZE, "budget %d exceeds WKV_MAX_BUDGET %d", o.budget, WKV_MAX_BUDGET);
+    if (o.recent_window < 1 || o.recent_window > o.budget)
+        return fail(WKV_EINVAL, "recent_window must be in 1..budget");
+    if (o.n_sink < 0 || (long long)o.n_sink + o.recent_window > o.budget)
+        return fail(WKV_EINVAL, "n_sink must be >= 0 with n_sink + recent_window <= budget");
+    if (o.score_mode < 0 || o.score_mode > 2) return fail(WKV_EINVAL, "unknown score_mode");
+    if (o.merge_mode < 0 || o.merge_mode > 1) return fail(WKV_EINVAL, "unknown merge_mode");
+    if (o.score_mode != WKV_SCORE_AVERAGE && o.merge_mode != WKV_MERGE_NONE)
+        return fail(WKV_EINVAL, "cumulative / last-step scoring are eviction rules: use WKV_MERGE_NONE");
+    if (o.log_capacity < 0) return fail(WKV_EINVAL, "log_capacity must be >= 0");
+    for (int r : o.reserved) if (r != 0) return fail(WKV_EINVAL, "reserved fields must be zero");
+    int th = o.threads;
+    const int units = o.batch * o.heads;
+    if (th == 0) th = units >= 1024 ? 256 : units >= 512 ? 512 : 1024;
+    if (th != 256 && th != 512 && th != 1024) return fail(WKV_EINVAL, "threads must be 256, 512 or 1024");
+    if (o.threads == 0)
+        while (th > 256 && wkv_step_lds_bytes(o.budget + 1, o.dtype, o.head_dim, th) > LDS_LIMIT) th /= 2;
+    if (wkv_step_lds_bytes(o.budget + 1, o.dtype, o.head_dim, th) > LDS_LIMIT)
+        return fail(WKV_ESIZE, "score row of %d slots does not fit the 64 KiB LDS staging at %d threads", o.budget + 1, th);
+    *threads = th;
+    return WKV_OK;
+}
+
+struct Sizes { size_t kv, a, i32, unit_i32, log, status, total; };
+
+Sizes sizes(const wkv_options& o)
+{
+    const size_t units = (size_t)o.batch * o.heads, cap = (size_t)o.budget + 1;
+    const size_t logc = o.log_capacity ? o.log_capacity : 1024;
+    Sizes s;
+    s.kv = units * cap * o.head_dim * dtype_bytes(o.dtype);
+    s.a = units * cap * sizeof(double);
+    s.i32 = units * cap * sizeof(int32_t);
+    s.unit_i32 = units * sizeof(int32_t);
+    s.log = logc * units * sizeof(int32_t);
+    s.status = 2 * sizeof(int32_t);
+    s.total = 2 * s.kv + s.a + 2 * s.i32 + s.unit_i32 + 2 * s.log + s.status;
+    return s;
+}
+
+}  // namespace
+
+struct wkv_handle {
+    wkv_options opt;
+    WkvCache c;
+    int device;
+    int threads;
+    int64_t t;        // tokens processed
+};
+
+extern "C" {
+
+const char* wkv_last_error(void) { return g_err.c_str(); }
+int wkv_version(void) { return 100; }
+
+size_t wkv_workspace_bytes(const wkv_options* opt)
+{
+    int th;
+    if (!opt || validate(*opt, &th) != WKV_OK) return 0;
+    return sizes(*opt).total;
+}
+
+size_t wkv_step_bytes(const wkv_options* opt)
+{
+    int th;
+    if (!opt || validate(*opt, &th) != WKV_OK) return 0;
+    const size_t units = (size_t)opt->batch * opt->heads, L = (size_t)opt->budget + 1;
+    const size_t row = (size_t)opt->head_dim * dtype_bytes(opt->dtype);
+    // per slot: K row + V row + score sum read and written (fp64) + position read
+    // per unit: q, k_new, v_new in, out out, K/V rows of the new token written,
+    //           merge reads two V rows and writes one
+    return units * (L * (2 * row + 16 + 4) + 4 * row + 2 * row + 3 * row);
+}
+
+int wkv_create_ex(wkv_handle** hp, const wkv_options* opt)
+{
+    if (!hp || !opt) return fail(WKV_EINVAL, "null argument");
+    int threads;
+    int rc = validate(*opt, &threads);
+    if (rc != WKV_OK) return rc;
+    wkv_handle* h = new (std::nothrow) wkv_handle();
+    if (!h) return fail(WKV_ENOMEM, "host allocation failed");
+    h->opt = *opt;
+    if (h->opt.log_capacity == 0) h->opt.log_capacity = 1024;
+    h->threads = threads;
+    h->t = 0;
+    hipError_t e = hipGetDevice(&h->device);
+    if (e != hipSuccess) {
+        delete h;
+        return fail(WKV_EHIP, "hipGetDevice: %s", hipGetErrorString(e));
+    }
+    const Sizes s = sizes(h->opt);
+    WkvCache& c = h->c;
+    memset(&c, 0, sizeof c);
+    c.units = opt->batch * opt->heads; c.cap = opt->budget + 1; c.m = opt->budget;
+    c.R = opt->recent_window; c.n_sink = opt->n_sink; c.score_mode = opt->score_mode;
+    c.merge_mode = opt->merge_mode; c.log_cap = h->opt.log_capacity;
+
+    struct { void** p; size_t n; int fill; } bufs[] = {
+        { &c.K, s.kv, 0 }, { &c.V, s.kv, 0 }, { (void**)&c.a, s.a, 0 },
+        { (void**)&c.pos, s.i32, 0xFF }, { (void**)&c.nmerged, s.i32, 0 },
+        { (void**)&c.free_slot, s.unit_i32, 0 }, { (void**)&c.log_pos, s.log, 0xFF },
+        { (void**)&c.log_slot, s.log, 0xFF }, { (void**)&c.status, s.status, 0 },
+    };
+    for (auto& b : bufs) {
+        e = hipMalloc(b.p, b.n);
+        if (e == hipSuccess) e = hipMemset(*b.p, b.fill, b.n);
+        if (e != hipSuccess) {
+            const bool oom = (e == hipErrorOutOfMemory);
+            rc = fail(oom ? WKV_ENOMEM : WKV_EHIP, "device allocation of %zu bytes: %s", b.n, hipGetErrorString(e));
+            (void)hipGetLastError();
+            for (auto& b2 : bufs) if (*b2.p) (void)hipFree(*b2.p);
+            delete h;
+            return rc;
+        }
+    }
+    std::vector<int32_t> fs(c.units, c.m);      // first compression happens with the new token in slot m
+    e = hipMemcpy(c.free_slot, fs.data(), s.unit_i32, hipMemcpyHostToDevice);
+    if (e != hipSuccess) {
+        rc = fail(WKV_EHIP, "hipMemcpy: %s", hipGetErrorString(e));
+        for (auto& b2 : bufs) (void)hipFree(*b2.p);
+        delete h;
+        return rc;
+    }
+    *hp = h;
+    return WKV_OK;
+}
+
+int wkv_create(wkv_handle** h, int batch, int heads, int head_dim, int budget, int recent_window, int dtype)
+{
+    wkv_options o;
+    memset(&o, 0, sizeof o);
+    o.batch = batch; o.heads = heads; o.head_dim = head_dim; o.budget = budget;
+    o.recent_window = recent_window; o.dtype = dtype;
+    return wkv_create_ex(h, &o);
+}
+
+int wkv_step(wkv_handle* h, const void* q, const void* k_new, const void* v_new, void* out, void* stream)
+{
+    if (!h) return fail(WKV_EINVAL, "null handle");
+    if (!q || !k_new || !v_new || !out) return fail(WKV_EINVAL, "null device pointer");
+    if ((((uintptr_t)q | (uintptr_t)k_new | (uintptr_t)v_new | (uintptr_t)out) & 15) != 0)
+        return fail(WKV_EINVAL, "q, k_new, v_new and out must be 16-byte aligned");
+    if (h->t >= 0x7FFFFFF0LL) return fail(WKV_ESIZE, "token counter would overflow");
+    int dev;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return fail(WKV_EHIP, "hipGetDevice: %s", hipGetErrorString(e));
+    if (dev != h->device) return fail(WKV_EINVAL, "handle belongs to device %d, current device is %d", h->device, dev);
+    e = wkv_launch_step(h->c, h->opt.dtype, h->opt.head_dim, h->threads, q, k_new, v_new, out, h->t,
+                        (hipStream_t)stream);
+    if (e != hipSuccess) return fail(WKV_EHIP, "kernel launch: %s", hipGetErrorString(e));
+    h->t += 1;
+    return WKV_OK;
+}
+
+int wkv_state(wkv_handle* h, int what, void* dst, size_t bytes)
+{
+    if (!h || !dst) return fail(WKV_EINVAL, "null argument");
+    const WkvCache& c = h->c;
+    const size_t units = c.units, cap = c.cap;
+    const int64_t T = h->t;
+    const size_t len = (size_t)std::min<int64_t>(T, c.m);
+    if (what == WKV_STEP) {
+        if (bytes < sizeof(int64_t)) return fail(WKV_ESIZE, "need 8 bytes");
+        memcpy(dst, &T, sizeof T);
+        return WKV_OK;
+    }
+    if (what == WKV_LEN) {
+        if (bytes < sizeof(int32_t)) return fail(WKV_ESIZE, "need 4 bytes");
+        const int32_t l = (int32_t)len;
+        memcpy(dst, &l, sizeof l);
+        return WKV_OK;
+    }
+    hipError_t e = hipDeviceSynchronize();
+    if (e != hipSuccess) return fail(WKV_EHIP, "hipDeviceSynchronize: %s", hipGetErrorString(e));
+
+    if (what == WKV_STATUS) {
+        if (bytes < 2 * sizeof(int32_t)) return fail(WKV_ESIZE, "need 8 bytes");
+        e = hipMemcpy(dst, c.status, 2 * sizeof(int32_t), hipMemcpyDeviceToHost);
+        return e == hipSuccess ? WKV_OK : fail(WKV_EHIP, "hipMemcpy: %s", hipGetErrorString(e));
+    }
+    if (what == WKV_EVICT_POS || what == WKV_EVICT_SLOT) {
+        if (bytes % (4 * units) != 0) return fail(WKV_EINVAL, "bytes must be a multiple of 4*units");
+        const int64_t n = (int64_t)(bytes / (4 * units));
+        if (n > std::min<int64_t>(T, c.log_cap))
+            return fail(WKV_ESIZE, "asked for %lld steps of log, %lld available", (long long)n,
+                        (long long)std::min<int64_t>(T, c.log_cap));
+        const int32_t* src = (what == WKV_EVICT_POS) ? c.log_pos : c.log_slot;
+        for (int64_t s = T - n; s < T; ++s) {       // ring: at most two contiguous pieces; keep it simple
+            e = hipMemcpy((char*)dst + (size_t)(s - (T - n)) * units * 4, src + (size_t)(s % c.log_cap) * units,
+                          units * 4, hipMemcpyDeviceToHost);
+            if (e != hipSuccess) return fail(WKV_EHIP, "hipMemcpy: %s", hipGetErrorString(e));
+        }
+        return WKV_OK;
+    }
+
+    const size_t d = h->opt.head_dim, eb = dtype_bytes(h->opt.dtype);
+    size_t need;
+    switch (what) {
+    case WKV_K: case WKV_V: need = units * len * d * eb; break;
+    case WKV_SCORE_SUM: need = units * len * sizeof(double); break;
+    case WKV_COUNT: case WKV_POS: case WKV_NMERGED: need = units * len * sizeof(int32_t); break;
+    default: return fail(WKV_EINVAL, "unknown state item %d", what);
+    }
+    if (bytes < need) return fail(WKV_ESIZE, "need %zu bytes, got %zu", need, bytes);
+    if (len == 0) return WKV_OK;
+
+    // token order of the live slots of every unit
+    std::vector<int32_t> pos(units * cap), fslot(units);
+    e = hipMemcpy(pos.data(), c.pos, pos.size() * 4, hipMemcpyDeviceToHost);
+    if (e == hipSuccess) e = hipMemcpy(fslot.data(), c.free_slot, units * 4, hipMemcpyDeviceToHost);
+    if (e != hipSuccess) return fail(WKV_EHIP, "hipMemcpy: %s", hipGetErrorString(e));
+    const size_t used = (size_t)std::min<int64_t>(T, (int64_t)cap);
+    std::vector<int32_t> order(units * len);
+    std::vector<int32_t> idx;
+    for (size_t u = 0; u < units; ++u) {
+        idx.clear();
+        for (size_t i = 0; i < used; ++i)
+            if (!(T > c.m && (int32_t)i == fslot[u])) idx.push_back((int32_t)i);
+        if (idx.size() != len) return fail(WKV_EHIP, "inconsistent cache state in unit %zu", u);
+        const int32_t* pu = pos.data() + u * cap;
+        std::sort(idx.begin(), idx.end(), [pu](int32_t x, int32_t y) { return pu[x] < pu[y]; });
+        std::copy(idx.begin(), idx.end(), order.begin() + u * len);
+    }
+
+    auto gather = [&](const void* dev, size_t elem, auto&& emit) -> int {
+        std::vector<char> raw(units * cap * elem);
+        hipError_t e2 = hipMemcpy(raw.data(), dev, raw.size(), hipMemcpyDeviceToHost);
+        if (e2 != hipSuccess) return fail(WKV_EHIP, "hipMemcpy: %s", hipGetErrorString(e2));
+        for (size_t u = 0; u < units; ++u)
+            for (size_t l = 0; l < len; ++l)
+                emit(u * len + l, raw.data() + (u * cap + order[u * len + l]) * elem);
+        return WKV_OK;
+    };
+    switch (what) {
+    case WKV_K: case WKV_V: {
+        const size_t rb = d * eb;
+        return gather(what == WKV_K ? c.K : c.V, rb,
+                      [&](size_t o, const char* src) { memcpy((char*)dst + o * rb, src, rb); });
+    }
+    case WKV_SCORE_SUM:
+        return gather(c.a, sizeof(double),
+                      [&](size_t o, const char* src) { memcpy((char*)dst + o * 8, src, 8); });
+    case WKV_POS:
+        return gather(c.pos, 4, [&](size_t o, const char* src) { memcpy((char*)dst + o * 4, src, 4); });
+    case WKV_NMERGED:
+        return gather(c.nmerged, 4, [&](size_t o, const char* src) { memcpy((char*)dst + o * 4, src, 4); });
+    case WKV_COUNT:     // n = steps attended = tokens - pos (every live slot is attended once per step)
+        return gather(c.pos, 4, [&](size_t o, const char* src) {
+            int32_t p; memcpy(&p, src, 4);
+            const int32_t n = (int32_t)(T - p);
+            memcpy((char*)dst + o * 4, &n, 4);
+        });
+    }
+    return fail(WKV_EINVAL, "unknown state item %d", what);
+}
+
+int wkv_destroy(wkv_handle* h)
+{
+    if (!h) return WKV_OK;
+    (void)hipDeviceSynchronize();
+    WkvCache& c = h->c;
+    void* bufs[] = { c.K, c.V, c.a, c.pos, c.nmerged, c.free_slot, c.log_pos, c.log_slot, c.status };
+    for (void* b : bufs) if (b) (void)hipFree(b);
+    delete h;
+    return WKV_OK;
+}
+
+}  // extern "C"

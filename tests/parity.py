@@ -1,0 +1,135 @@
+"""Shared machinery of the GPU parity tests: stream a synthetic configuration
+through libwkv (via the C ABI binding) and through the CPU oracle, and compare.
+
+Acceptance bars (stated once here, used by every parity test):
+  * eviction indices (evicted token, its rank in token order): bit-exact.  A
+    disagreement is tolerated only if, in the oracle's own fp64 state, the two
+    candidates' scores differ by at most 1e-6 relative; it is then logged and
+    the oracle continues from the GPU's choice for that step.
+  * retained keys, token positions, counts, merge counts: bit-exact.
+  * attention outputs and merged values: |gpu - ref| <= rtol*|ref| + atol_rel*max|ref row|
+    with rtol = 2e-3 for fp16/bf16 (fp32 accumulation) and 1e-5 for fp32.  The
+    second term covers elements that nearly cancel: the fp32 accumulation error
+    is relative to sum_i p_i |V_i|, not to the (possibly tiny) result.
+  * score sums a: 1e-9 relative (both sides accumulate in fp64).
+"""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+import oracle
+from paper_2503_01330_amd import binding as wkv
+from paper_2503_01330_amd import synth
+
+RTOL = {"fp32": 1e-5, "fp16": 2e-3, "bf16": 2e-3}
+ATOL_REL = {"fp32": 1e-6, "fp16": 1e-5, "bf16": 1e-5}
+NEAR_TIE = 1e-6
+
+_TORCH_VIEW = {"fp32": torch.float32, "fp16": torch.float16, "bf16": torch.bfloat16}
+
+
+def to_device(x: np.ndarray, dtype: str) -> torch.Tensor:
+    t = torch.from_numpy(x).cuda()
+    return t.view(torch.bfloat16) if dtype == "bf16" else t
+
+
+def out_to_f64(t: torch.Tensor, dtype: str) -> np.ndarray:
+    return t.to(torch.float64).cpu().numpy()
+
+
+def gpu_stream(cfg, layer=0, units_sel=None, steps=None, progress=None, **create_kw):
+    """Stream cfg through a libwkv handle.  Returns dict(out [T,U',d] f64 for the selected
+    units, evict_pos / evict_slot [T, units] i32, cache (open handle), inputs of the
+    selected units as exact fp32)."""
+    steps = cfg.steps if steps is None else steps
+    st = synth.Stream(cfg, layer)
+    cache = wkv.Cache(cfg.batch, cfg.heads, cfg.head_dim, cfg.budget, cfg.recent,
+                      synth.DTYPE_CODE[cfg.dtype], **create_kw)
+    sel = np.arange(cfg.units) if units_sel is None else np.asarray(units_sel)
+    outs, evp, evs, qs, ks, vs = [], [], [], [], [], []
+    t = 0
+    while t < steps:
+        c = t // synth.CHUNK
+        q, k, v = st.chunk(c)
+        n = min(q.shape[0], steps - t)
+        q, k, v = q[:n], k[:n], v[:n]
+        tq, tk, tv = (to_device(x, cfg.dtype) for x in (q, k, v))
+        out = torch.empty_like(tq)
+        for i in range(n):
+            cache.step(tq[i], tk[i], tv[i], out[i])
+        torch.cuda.synchronize()
+        p, s = cache.evictions(n)
+        evp.append(p); evs.append(s)
+        outs.append(out_to_f64(out[:, torch.from_numpy(sel).cuda()], cfg.dtype))
+        for dst, src in ((qs, q), (ks, k), (vs, v)):
+            dst.append(synth.storage_to_f32(src[:, sel], cfg.dtype))
+        t += n
+        if progress:
+            print(f"  [{progress}] gpu step {t}/{steps}", flush=True)
+    return dict(out=np.concatenate(outs), evict_pos=np.concatenate(evp), evict_slot=np.concatenate(evs),
+                cache=cache, q=np.concatenate(qs), k=np.concatenate(ks), v=np.concatenate(vs), sel=sel)
+
+
+def oracle_stream(cfg, g, forced=None, **orc_kw):
+    orc = oracle.Oracle(len(g["sel"]), cfg.head_dim, cfg.budget, cfg.recent, storage=cfg.dtype, **orc_kw)
+    res = orc.run(g["q"], g["k"], g["v"], forced_pos=forced)
+    res["orc"] = orc
+    return res
+
+
+def check_outputs(got, ref, dtype, what="out"):
+    scale = np.abs(ref).max(axis=-1, keepdims=True)
+    err = np.abs(got - ref)
+    bound = RTOL[dtype] * np.abs(ref) + ATOL_REL[dtype] * scale
+    bad = err > bound
+    assert not bad.any(), (f"{what}: {bad.sum()} elements out of tolerance, worst error "
+                           f"{err.max():.3e} at {np.unravel_index(np.argmax(err - bound), err.shape)}")
+    return float((err / np.maximum(scale, 1e-300)).max())
+
+
+def compare(cfg, g, check_state=True, log=print, **orc_kw):
+    """Full comparison of a gpu_stream result with the oracle on the same inputs."""
+    sel = g["sel"]
+    gp, gs = g["evict_pos"][:, sel], g["evict_slot"][:, sel]
+    ref = oracle_stream(cfg, g, **orc_kw)
+    near_ties = 0
+    if not np.array_equal(gp, ref["evict_pos"]):
+        # classify: rerun the oracle following the GPU's choices, every override must be a near-tie
+        forced = np.where(gp >= 0, gp, -1).astype(np.int32)
+        ref = oracle_stream(cfg, g, forced=forced, **orc_kw)
+        ov = ~np.isnan(ref["forced_score"])
+        gap = np.abs(ref["forced_score"][ov] - ref["evict_score"][ov]) / np.abs(ref["evict_score"][ov])
+        for (t, u), gv in zip(np.argwhere(ov), gap):
+            log(f"near-tie: step {t} unit {sel[u]} relative score gap {gv:.3e}")
+        assert (gap <= NEAR_TIE).all(), f"eviction index mismatch beyond near-tie: worst gap {gap.max():.3e}"
+        near_ties = int(ov.sum())
+    assert np.array_equal(gp, ref["evict_pos"]), "evicted token indices differ"
+    assert np.array_equal(gs, ref["evict_slot"]), "evicted slot ranks differ"
+    worst = check_outputs(g["out"], ref["out"], cfg.dtype)
+    stats = dict(near_ties=near_ties, out_err=worst,
+                 min_gap=float(np.nanmin((ref["runner_up"] - ref["evict_score"]) / ref["evict_score"]))
+                 if np.isfinite(ref["evict_score"]).any() else float("nan"))
+    if check_state:
+        cache = g["cache"]
+        T = g["out"].shape[0]
+        assert cache.tokens == T and cache.length == min(T, cfg.budget)
+        K = cache.state(wkv.WKV_K)[sel]; V = cache.state(wkv.WKV_V)[sel]
+        a = cache.state(wkv.WKV_SCORE_SUM)[sel]; n = cache.state(wkv.WKV_COUNT)[sel]
+        pos = cache.state(wkv.WKV_POS)[sel]; nm = cache.state(wkv.WKV_NMERGED)[sel]
+        Kf = synth.storage_to_f32(K, cfg.dtype).astype(np.float64)
+        Vf = synth.storage_to_f32(V, cfg.dtype).astype(np.float64)
+        v_exact = 0
+        for i in range(len(sel)):
+            st = ref["orc"].state(i)
+            assert np.array_equal(pos[i], st["pos"]), "retained token positions differ"
+            assert np.array_equal(n[i], st["n"]), "counts differ"
+            assert np.array_equal(nm[i], st["nmerged"]), "merge counts differ"
+            assert np.array_equal(Kf[i], st["K"]), "retained keys differ"
+            assert np.allclose(a[i], st["a"], rtol=1e-9, atol=0), "score sums differ"
+            check_outputs(Vf[i], st["V"], cfg.dtype, what="merged values")
+            v_exact += int(np.array_equal(Vf[i], st["V"]))
+        stats["v_bit_exact_units"] = v_exact
+        status = cache.state(wkv.WKV_STATUS)
+        assert status[1] == 0, "non-finite scores flagged"
+    return stats

@@ -1,0 +1,70 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every
+symbol the header declares, and rejects bad arguments with error codes."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_2503_01330_amd import binding as wkv
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_every_declared_symbol_is_exported():
+    header = open(os.path.join(ROOT, "include", "wkv.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(wkv_[a-z_]+)\s*\(", header))
+    assert declared == set(wkv.EXPORTS)
+    lib = C.CDLL(wkv.LIB_PATH)
+    for name in declared:
+        assert hasattr(lib, name), name
+    assert wkv.wkv_version() >= 100
+
+
+def test_header_constants_match_binding():
+    header = open(os.path.join(ROOT, "include", "wkv.h")).read()
+    for name, val in re.findall(r"#define\s+(WKV_[A-Z0-9_]+)\s+(-?\d+)", header):
+        assert getattr(wkv, name) == int(val), name
+
+
+def test_options_struct_layout():
+    assert C.sizeof(wkv.wkv_options) == 16 * 4
+
+
+@pytest.mark.parametrize("kw,code", [
+    (dict(batch=0), wkv.WKV_EINVAL), (dict(heads=-1), wkv.WKV_EINVAL),
+    (dict(head_dim=96), wkv.WKV_EINVAL), (dict(head_dim=256, dtype=wkv.WKV_FP32), wkv.WKV_EINVAL),
+    (dict(dtype=7), wkv.WKV_EINVAL), (dict(budget=0), wkv.WKV_EINVAL),
+    (dict(budget=wkv.WKV_MAX_BUDGET + 1), wkv.WKV_ESIZE),
+    (dict(recent_window=0), wkv.WKV_EINVAL), (dict(recent_window=65), wkv.WKV_EINVAL),
+    (dict(n_sink=-1), wkv.WKV_EINVAL), (dict(n_sink=60, recent_window=16), wkv.WKV_EINVAL),
+    (dict(score_mode=3), wkv.WKV_EINVAL), (dict(merge_mode=2), wkv.WKV_EINVAL),
+    (dict(score_mode=1, merge_mode=0), wkv.WKV_EINVAL), (dict(threads=128), wkv.WKV_EINVAL),
+    (dict(log_capacity=-5), wkv.WKV_EINVAL),
+])
+def test_invalid_options_are_rejected_before_touching_the_gpu(kw, code):
+    base = dict(batch=1, heads=4, head_dim=64, budget=64, recent_window=16, dtype=wkv.WKV_FP32)
+    base.update(kw)
+    opt = wkv.make_options(**base)
+    assert wkv.wkv_workspace_bytes(opt) == 0
+    with pytest.raises(wkv.WkvError) as e:
+        wkv.wkv_create_ex(opt)
+    assert e.value.code == code and wkv.wkv_last_error()
+
+
+def test_null_arguments():
+    lib = C.CDLL(wkv.LIB_PATH)
+    assert lib.wkv_create_ex(None, None) == wkv.WKV_EINVAL
+    assert lib.wkv_step(None, None, None, None, None, None) == wkv.WKV_EINVAL
+    assert lib.wkv_state(None, 0, None, 0) == wkv.WKV_EINVAL
+    assert lib.wkv_destroy(None) == wkv.WKV_OK
+
+
+def test_size_arithmetic():
+    # Llama-2-7B-shaped layer, batch 8, budget 410 (the stacked configuration)
+    opt = wkv.make_options(8, 32, 128, 410, 32, wkv.WKV_FP16)
+    units, L, row = 256, 411, 256
+    assert wkv.wkv_step_bytes(opt) == units * (L * (2 * row + 20) + 9 * row)
+    kv = 2 * units * L * row
+    assert kv < wkv.wkv_workspace_bytes(opt) < kv * 1.1 + (1 << 22)

@@ -1,0 +1,124 @@
+"""GPU parity: libwkv (through the C ABI) against the CPU oracle, element by element.
+
+Small cases compare every unit and the final cache state; the full-size
+configurations run the GPU on every unit in the launch configuration the
+benchmark uses and compare a sample of units that the oracle can afford.
+"""
+import numpy as np
+import pytest
+import torch
+
+from paper_2503_01330_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+if torch.cuda.is_available():
+    import parity
+    from paper_2503_01330_amd import binding as wkv
+
+
+def _run(cfg, units_sel=None, layer=0, label=None, **kw):
+    g = parity.gpu_stream(cfg, layer=layer, units_sel=units_sel, progress=label, **kw)
+    try:
+        okw = {k: kw[k] for k in ("n_sink", "score_mode", "merge_mode") if k in kw}
+        stats = parity.compare(cfg, g, **okw)
+    finally:
+        g["cache"].close()
+    print(f"\n  {cfg.name}: {stats}", flush=True)
+    return stats
+
+
+def test_cfg1_tiny_fp32_full_stream():
+    stats = _run(synth.CONFIGS["cfg1"])
+    assert stats["near_ties"] == 0
+
+
+@pytest.mark.parametrize("threads", [256, 512, 1024])
+def test_cfg1_all_workgroup_sizes(threads):
+    _run(synth.scaled(synth.CONFIGS["cfg1"], steps=200), threads=threads)
+
+
+@pytest.mark.parametrize("dtype", ["fp16", "bf16", "fp32"])
+@pytest.mark.parametrize("d", [64, 128, 256])
+def test_head_dims_and_dtypes(dtype, d):
+    if dtype == "fp32" and d == 256:
+        pytest.skip("fp32 rows of 256 elements are not built")
+    cfg = synth.StreamConfig(f"d{d}{dtype}", 7000 + d, 2, 3, d, dtype, 300, 37, 5)
+    _run(cfg)
+
+
+@pytest.mark.parametrize("m,R", [(1, 1), (2, 1), (2, 2), (5, 5), (33, 1), (64, 64), (100, 17)])
+def test_edge_budgets_and_windows(m, R):
+    """degenerate caches: a single slot, window = budget (FIFO fold), window = 1
+    (Algorithm 1 as printed, where the right neighbour can be the incoming token)."""
+    cfg = synth.StreamConfig(f"m{m}R{R}", 7100 + m, 1, 5, 128, "fp16", 3 * m + 70, m, R)
+    _run(cfg)
+
+
+def test_fill_phase_only_is_full_attention():
+    """budget >= stream: nothing is evicted, every output is plain softmax attention."""
+    cfg = synth.StreamConfig("fill", 7200, 2, 4, 128, "bf16", 150, 200, 8)
+    stats = _run(cfg)
+    assert np.isnan(stats["min_gap"])
+
+
+def test_ragged_tail_lengths():
+    """slot counts that are not multiples of the 4-rows-per-wave tile or of the workgroup's stride"""
+    for m in (63, 65, 129, 255, 257):
+        cfg = synth.StreamConfig(f"rag{m}", 7300 + m, 1, 2, 128, "fp16", m + 40, m, 3)
+        _run(cfg, threads=256)
+
+
+def test_sink_protection_and_eviction_variants():
+    cfg = synth.StreamConfig("sink", 7400, 1, 6, 128, "fp16", 260, 48, 8)
+    _run(cfg, n_sink=4)
+    _run(cfg, merge_mode=wkv.WKV_MERGE_NONE)
+    _run(cfg, merge_mode=wkv.WKV_MERGE_NONE, score_mode=wkv.WKV_SCORE_CUMULATIVE)
+    _run(cfg, merge_mode=wkv.WKV_MERGE_NONE, score_mode=wkv.WKV_SCORE_LAST)
+
+
+def test_determinism_same_stream_twice():
+    cfg = synth.scaled(synth.CONFIGS["cfg2"], steps=1100, heads=8, budget=300)
+    a = parity.gpu_stream(cfg); b = parity.gpu_stream(cfg)
+    try:
+        assert np.array_equal(a["evict_pos"], b["evict_pos"])
+        assert np.array_equal(a["out"], b["out"])
+        assert np.array_equal(a["cache"].state(wkv.WKV_V), b["cache"].state(wkv.WKV_V))
+        assert np.array_equal(a["cache"].state(wkv.WKV_SCORE_SUM), b["cache"].state(wkv.WKV_SCORE_SUM))
+    finally:
+        a["cache"].close(); b["cache"].close()
+
+
+def test_cfg2_llama_layer_full_stream():
+    stats = _run(synth.CONFIGS["cfg2"], label="cfg2")
+    assert stats["near_ties"] == 0
+
+
+def test_cfg3_stack_sampled_layers_and_units():
+    """Two of the 32 layers (first and last), full 4096-token stream on all 256 units in
+    the benchmark's launch shape; 6 sampled units per layer go through the oracle."""
+    cfg = synth.CONFIGS["cfg3"]
+    for layer in (0, 31):
+        sel = np.random.default_rng(layer).choice(cfg.units, 6, replace=False)
+        stats = _run(cfg, units_sel=np.sort(sel), layer=layer, label=f"cfg3 layer {layer}")
+        assert stats["near_ties"] == 0
+
+
+def test_cfg4_long_stream_sampled_units():
+    cfg = synth.CONFIGS["cfg4"]
+    sel = np.array([0, 37, 90, 127])
+    g = parity.gpu_stream(cfg, units_sel=sel, progress="cfg4")
+    try:
+        stats = parity.compare(cfg, g)
+        pos = g["cache"].state(wkv.WKV_POS)
+    finally:
+        g["cache"].close()
+    print(f"\n  cfg4: {stats}", flush=True)
+    # attention-sink heavy hitters (keys with 8x norm) survive by score alone
+    assert (pos[:, :4] == np.arange(4)).all()
+
+
+def test_cfg5_batched_bf16_sampled_units():
+    cfg = synth.CONFIGS["cfg5"]
+    sel = np.sort(np.random.default_rng(5).choice(cfg.units, 8, replace=False))
+    _run(cfg, units_sel=sel, label="cfg5")
