@@ -8,7 +8,8 @@ Acceptance bars (stated once here, used by every parity test):
     the oracle continues from the GPU's choice for that step.
   * retained keys, token positions, counts, merge counts: bit-exact.
   * attention outputs and merged values: |gpu - ref| <= rtol*|ref| + atol_rel*max|ref row|
-    with rtol = 2e-3 for fp16/bf16 (fp32 accumulation) and 1e-5 for fp32.  The
+    with rtol = 2e-3 for fp16 (fp32 accumulation), 2^-8 for bf16 (its unit roundoff, see
+    below) and 1e-5 for fp32.  The
     second term covers elements that nearly cancel: the fp32 accumulation error
     is relative to sum_i p_i |V_i|, not to the (possibly tiny) result.
   * score sums a: 1e-9 relative (both sides accumulate in fp64).
@@ -22,7 +23,15 @@ import oracle
 from paper_2503_01330_amd import binding as wkv
 from paper_2503_01330_amd import synth
 
-RTOL = {"fp32": 1e-5, "fp16": 2e-3, "bf16": 2e-3}
+# 2e-3 / 1e-5 are the stated targets.  bf16 carries 8 significand bits, so merely
+# storing a result in bf16 moves it by up to 2^-8 = 3.9e-3 relative: no bf16 output can
+# be within 2e-3 of an unrounded fp64 value element by element.  For bf16 the bar is
+# therefore the format's own unit roundoff (the result must be the correctly rounded
+# value or its neighbour where the fp32 accumulation error straddles a rounding
+# boundary); the fraction of elements that equal the rounded reference bit for bit is
+# reported next to it.
+UNIT_ROUNDOFF = {"fp32": 2.0 ** -24, "fp16": 2.0 ** -11, "bf16": 2.0 ** -8}
+RTOL = {"fp32": 1e-5, "fp16": 2e-3, "bf16": max(2e-3, 2.0 ** -8)}
 ATOL_REL = {"fp32": 1e-6, "fp16": 1e-5, "bf16": 1e-5}
 NEAR_TIE = 1e-6
 
@@ -88,6 +97,17 @@ def check_outputs(got, ref, dtype, what="out"):
     return float((err / np.maximum(scale, 1e-300)).max())
 
 
+def exact_fraction(got, ref, dtype):
+    """Fraction of elements that equal the reference rounded to the storage format."""
+    if dtype == "fp16":
+        r = ref.astype(np.float16).astype(np.float64)
+    elif dtype == "bf16":
+        r = synth.bf16_bits_to_f32(synth.f32_to_bf16_bits(ref.astype(np.float32))).astype(np.float64)
+    else:
+        r = ref.astype(np.float32).astype(np.float64)
+    return float((got == r).mean())
+
+
 def compare(cfg, g, check_state=True, log=print, **orc_kw):
     """Full comparison of a gpu_stream result with the oracle on the same inputs."""
     sel = g["sel"]
@@ -107,7 +127,7 @@ def compare(cfg, g, check_state=True, log=print, **orc_kw):
     assert np.array_equal(gp, ref["evict_pos"]), "evicted token indices differ"
     assert np.array_equal(gs, ref["evict_slot"]), "evicted slot ranks differ"
     worst = check_outputs(g["out"], ref["out"], cfg.dtype)
-    stats = dict(near_ties=near_ties, out_err=worst,
+    stats = dict(near_ties=near_ties, out_err=worst, out_exact=exact_fraction(g["out"], ref["out"], cfg.dtype),
                  min_gap=float(np.nanmin((ref["runner_up"] - ref["evict_score"]) / ref["evict_score"]))
                  if np.isfinite(ref["evict_score"]).any() else float("nan"))
     if check_state:
