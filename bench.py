@@ -1,0 +1,146 @@
+#!/usr/bin/env python3
+"""Benchmark of the WeightedKV decode step on one MI355X.
+
+A "step" is one generated token through the whole hot path: for the default
+workload (the 32-layer Llama-2-7B-shaped stack, batch 8, budget 410) that is 32
+wkv_step launches, one per layer, each doing append + attention + score update
++ select + merge for 256 (sequence, head) units.  Inputs are synthetic, seeded
+and already resident in HBM when the timed region starts.  Prints ONE JSON line.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0        # MI355X published HBM3E bandwidth
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="cfg3", choices=["cfg2", "cfg3", "cfg4", "cfg5"])
+    ap.add_argument("--layers", type=int, default=0, help="override the number of stacked layers")
+    ap.add_argument("--threads", type=int, default=0, help="workgroup size override (256/512/1024)")
+    ap.add_argument("--skip-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=12.0, help="target CPU time of the oracle leg")
+    return ap.parse_args()
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on exactly one GPU (units are independent and would shard "
+              "with no exchange, but no multi-GPU path exists); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2503_01330_amd import binding as wkv
+    from paper_2503_01330_amd import synth
+
+    cfg = synth.CONFIGS[args.workload]
+    layers = args.layers or cfg.layers
+    fill = cfg.budget                       # tokens streamed (untimed) until the cache is full
+    W, K = args.warmup, args.steps
+    total = fill + W + K
+    cfg = synth.scaled(cfg, steps=total, layers=max(layers, cfg.layers))
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    code = synth.DTYPE_CODE[cfg.dtype]
+    eb = synth.DTYPE_BYTES[cfg.dtype]
+
+    # ---- stage the whole synthetic stream in HBM, one [total, units, d] tensor triple per layer
+    t0 = time.perf_counter()
+    caches, bufs, ptrs = [], [], []
+    for layer in range(layers):
+        q, k, v = synth.Stream(cfg, layer).steps(0, total)
+        tq, tk, tv = (torch.from_numpy(x).to(dev) for x in (q, k, v))
+        out = torch.empty_like(tq)
+        bufs.append((tq, tk, tv, out))
+        ptrs.append(tuple(x.data_ptr() for x in (tq, tk, tv, out)))
+        caches.append(wkv.Cache(cfg.batch, cfg.heads, cfg.head_dim, cfg.budget, cfg.recent, code,
+                                threads=args.threads))
+    gen_s = time.perf_counter() - t0
+    stride = cfg.units * cfg.head_dim * eb
+    stream = torch.cuda.current_stream().cuda_stream
+    handles = [c.h for c in caches]
+    step = wkv.wkv_step
+
+    def run(t_lo, t_hi):
+        for t in range(t_lo, t_hi):
+            off = t * stride
+            for h, (pq, pk, pv, po) in zip(handles, ptrs):
+                step(h, pq + off, pk + off, pv + off, po + off, stream)
+
+    run(0, fill)                 # fill phase: cache grows to its budget
+    run(fill, fill + W)          # steady-state warmup
+    torch.cuda.synchronize()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    w0 = time.perf_counter()
+    ev0.record()
+    run(fill + W, total)
+    ev1.record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - w0
+    ev_ms = ev0.elapsed_time(ev1)
+
+    launches = K * layers
+    step_bytes = caches[0].step_bytes()                 # algorithmic bytes of one launch
+    kernel_us = ev_ms * 1e3 / launches                   # average launch duration incl. gaps (HIP events)
+    achieved = step_bytes / (kernel_us * 1e-6) / 1e9
+    tokens_per_s = cfg.batch * K / wall
+
+    result = {
+        "metric": "compressed-cache decode tokens/s at budget B; achieved HBM GB/s % of peak",
+        "value": round(tokens_per_s, 1), "unit": "tokens/s", "n_gpus": 1, "steps": K, "warmup": W,
+        "ms_per_step": round(wall * 1e3 / K, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": {"fp16": "f16 in, f32/f64 accumulate", "bf16": "bf16 in, f32/f64 accumulate",
+                                       "fp32": "f32 in, f64 accumulate"}[cfg.dtype],
+        "data": "synthetic",
+        "config": {"workload": f"{args.workload}: {layers} layer(s) x batch {cfg.batch} x {cfg.heads} heads x "
+                               f"{cfg.head_dim} {cfg.dtype}, budget {cfg.budget}, recent window {cfg.recent}, "
+                               f"steady state after a {fill}-token fill",
+                   "units_per_launch": cfg.units, "launches_per_step": layers,
+                   "threads_per_workgroup": caches[0].opt.threads or "auto",
+                   "input_staging_s": round(gen_s, 1)},
+        "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                     "kernel": "wkv_step_kernel", "bytes_per_launch": step_bytes,
+                     "avg_launch_us": round(kernel_us, 3)},
+    }
+
+    if not args.skip_cpu_baseline:
+        import oracle
+        # bounded sample: layer 0, every unit, steady-state steps after the same fill
+        st = synth.Stream(cfg, 0)
+        orc = oracle.Oracle(cfg.units, cfg.head_dim, cfg.budget, cfg.recent, storage=cfg.dtype)
+        q, k, v = (synth.storage_to_f32(x, cfg.dtype) for x in st.steps(0, fill))
+        orc.run(q, k, v, want_out=False)
+        probe = min(8, W + K)
+        q, k, v = (synth.storage_to_f32(x, cfg.dtype) for x in st.steps(fill, total))
+        c0 = time.perf_counter()
+        orc.run(q[:probe], k[:probe], v[:probe])
+        per = (time.perf_counter() - c0) / probe
+        n = int(max(1, min(W + K - probe, args.cpu_seconds / per)))
+        c0 = time.perf_counter()
+        orc.run(q[probe:probe + n], k[probe:probe + n], v[probe:probe + n])
+        cpu_s = time.perf_counter() - c0
+        result["cpu_baseline"] = {
+            "value": round(cfg.batch * n / (cpu_s * layers), 2), "unit": "tokens/s",
+            "cores": oracle.threads(), "kind": "oracle",
+            "sample": f"layer 0 of {layers}, all {cfg.units} units, {n} steady-state steps in {cpu_s:.1f} s "
+                      f"after the {fill}-token fill; scaled by 1/{layers} layers to whole-token rate",
+        }
+    for c in caches:
+        c.close()
+    print(json.dumps(result), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -55,30 +55,35 @@ int validate(const wkv_options& o, int* threads)
     for (int r : o.reserved) if (r != 0) return fail(WKV_EINVAL, "reserved fields must be zero");
     int th = o.threads;
     const int units = o.batch * o.heads;
-    if (th == 0) th = units >= 1024 ? 256 : units >= 512 ? 512 : 1024;
+    auto fits = [&](int n) {
+        return wkv_step_lds_bytes(o.budget, o.dtype, o.head_dim, n) <= LDS_LIMIT &&
+               o.budget + 1 <= wkv_step_max_entries(n);
+    };
+    if (th == 0) {
+        // few units: large workgroups so that one unit's rows are spread over many waves
+        th = units >= 1024 ? 256 : units >= 512 ? 512 : 1024;
+        while (th < 1024 && !fits(th)) th *= 2;
+    }
     if (th != 256 && th != 512 && th != 1024) return fail(WKV_EINVAL, "threads must be 256, 512 or 1024");
-    if (o.threads == 0)
-        while (th > 256 && wkv_step_lds_bytes(o.budget + 1, o.dtype, o.head_dim, th) > LDS_LIMIT) th /= 2;
-    if (wkv_step_lds_bytes(o.budget + 1, o.dtype, o.head_dim, th) > LDS_LIMIT)
-        return fail(WKV_ESIZE, "score row of %d slots does not fit the 64 KiB LDS staging at %d threads", o.budget + 1, th);
+    if (!fits(th))
+        return fail(WKV_ESIZE, "a score row of %d entries does not fit a workgroup of %d threads", o.budget + 1, th);
     *threads = th;
     return WKV_OK;
 }
 
-struct Sizes { size_t kv, a, i32, unit_i32, log, status, total; };
+struct Sizes { size_t kv, a, i32, log, status, total; };
 
 Sizes sizes(const wkv_options& o)
 {
-    const size_t units = (size_t)o.batch * o.heads, cap = (size_t)o.budget + 1;
+    const size_t units = (size_t)o.batch * o.heads, cap = (size_t)o.budget;
     const size_t logc = o.log_capacity ? o.log_capacity : 1024;
     Sizes s;
     s.kv = units * cap * o.head_dim * dtype_bytes(o.dtype);
     s.a = units * cap * sizeof(double);
     s.i32 = units * cap * sizeof(int32_t);
-    s.unit_i32 = units * sizeof(int32_t);
     s.log = logc * units * sizeof(int32_t);
     s.status = 2 * sizeof(int32_t);
-    s.total = 2 * s.kv + s.a + 2 * s.i32 + s.unit_i32 + 2 * s.log + s.status;
+    s.total = 2 * s.kv + s.a + 2 * s.i32 + 2 * s.log + s.status;
     return s;
 }
 
@@ -110,7 +115,7 @@ size_t wkv_step_bytes(const wkv_options* opt)
     if (!opt || validate(*opt, &th) != WKV_OK) return 0;
     const size_t units = (size_t)opt->batch * opt->heads, L = (size_t)opt->budget + 1;
     const size_t row = (size_t)opt->head_dim * dtype_bytes(opt->dtype);
-    // per slot: K row + V row + score sum read and written (fp64) + position read
+    // per attended entry: K row + V row + score sum read and written (fp64) + position read
     // per unit: q, k_new, v_new in, out out, K/V rows of the new token written,
     //           merge reads two V rows and writes one
     return units * (L * (2 * row + 16 + 4) + 4 * row + 2 * row + 3 * row);
@@ -136,14 +141,14 @@ int wkv_create_ex(wkv_handle** hp, const wkv_options* opt)
     const Sizes s = sizes(h->opt);
     WkvCache& c = h->c;
     memset(&c, 0, sizeof c);
-    c.units = opt->batch * opt->heads; c.cap = opt->budget + 1; c.m = opt->budget;
+    c.units = opt->batch * opt->heads; c.m = opt->budget;
     c.R = opt->recent_window; c.n_sink = opt->n_sink; c.score_mode = opt->score_mode;
     c.merge_mode = opt->merge_mode; c.log_cap = h->opt.log_capacity;
 
     struct { void** p; size_t n; int fill; } bufs[] = {
         { &c.K, s.kv, 0 }, { &c.V, s.kv, 0 }, { (void**)&c.a, s.a, 0 },
         { (void**)&c.pos, s.i32, 0xFF }, { (void**)&c.nmerged, s.i32, 0 },
-        { (void**)&c.free_slot, s.unit_i32, 0 }, { (void**)&c.log_pos, s.log, 0xFF },
+        { (void**)&c.log_pos, s.log, 0xFF },
         { (void**)&c.log_slot, s.log, 0xFF }, { (void**)&c.status, s.status, 0 },
     };
     for (auto& b : bufs) {
@@ -157,14 +162,6 @@ int wkv_create_ex(wkv_handle** hp, const wkv_options* opt)
             delete h;
             return rc;
         }
-    }
-    std::vector<int32_t> fs(c.units, c.m);      // first compression happens with the new token in slot m
-    e = hipMemcpy(c.free_slot, fs.data(), s.unit_i32, hipMemcpyHostToDevice);
-    if (e != hipSuccess) {
-        rc = fail(WKV_EHIP, "hipMemcpy: %s", hipGetErrorString(e));
-        for (auto& b2 : bufs) (void)hipFree(*b2.p);
-        delete h;
-        return rc;
     }
     *hp = h;
     return WKV_OK;
@@ -201,7 +198,7 @@ int wkv_state(wkv_handle* h, int what, void* dst, size_t bytes)
 {
     if (!h || !dst) return fail(WKV_EINVAL, "null argument");
     const WkvCache& c = h->c;
-    const size_t units = c.units, cap = c.cap;
+    const size_t units = c.units, cap = c.m;
     const int64_t T = h->t;
     const size_t len = (size_t)std::min<int64_t>(T, c.m);
     if (what == WKV_STEP) {
@@ -249,22 +246,16 @@ int wkv_state(wkv_handle* h, int what, void* dst, size_t bytes)
     if (bytes < need) return fail(WKV_ESIZE, "need %zu bytes, got %zu", need, bytes);
     if (len == 0) return WKV_OK;
 
-    // token order of the live slots of every unit
-    std::vector<int32_t> pos(units * cap), fslot(units);
+    // token order of the live slots (physical slots 0..len-1) of every unit
+    std::vector<int32_t> pos(units * cap);
     e = hipMemcpy(pos.data(), c.pos, pos.size() * 4, hipMemcpyDeviceToHost);
-    if (e == hipSuccess) e = hipMemcpy(fslot.data(), c.free_slot, units * 4, hipMemcpyDeviceToHost);
     if (e != hipSuccess) return fail(WKV_EHIP, "hipMemcpy: %s", hipGetErrorString(e));
-    const size_t used = (size_t)std::min<int64_t>(T, (int64_t)cap);
     std::vector<int32_t> order(units * len);
-    std::vector<int32_t> idx;
     for (size_t u = 0; u < units; ++u) {
-        idx.clear();
-        for (size_t i = 0; i < used; ++i)
-            if (!(T > c.m && (int32_t)i == fslot[u])) idx.push_back((int32_t)i);
-        if (idx.size() != len) return fail(WKV_EHIP, "inconsistent cache state in unit %zu", u);
+        int32_t* idx = order.data() + u * len;
+        std::iota(idx, idx + len, 0);
         const int32_t* pu = pos.data() + u * cap;
-        std::sort(idx.begin(), idx.end(), [pu](int32_t x, int32_t y) { return pu[x] < pu[y]; });
-        std::copy(idx.begin(), idx.end(), order.begin() + u * len);
+        std::sort(idx, idx + len, [pu](int32_t x, int32_t y) { return pu[x] < pu[y]; });
     }
 
     auto gather = [&](const void* dev, size_t elem, auto&& emit) -> int {
@@ -304,7 +295,7 @@ int wkv_destroy(wkv_handle* h)
     if (!h) return WKV_OK;
     (void)hipDeviceSynchronize();
     WkvCache& c = h->c;
-    void* bufs[] = { c.K, c.V, c.a, c.pos, c.nmerged, c.free_slot, c.log_pos, c.log_slot, c.status };
+    void* bufs[] = { c.K, c.V, c.a, c.pos, c.nmerged, c.log_pos, c.log_slot, c.status };
     for (void* b : bufs) if (b) (void)hipFree(b);
     delete h;
     return WKV_OK;

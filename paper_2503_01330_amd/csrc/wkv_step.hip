@@ -12,19 +12,29 @@
 //     for d=128 half precision) fully coalesced, and the 16-lane dot-product
 //     reduction is four DPP steps (quad_perm, quad_perm, row_half_mirror,
 //     row_mirror) with no LDS traffic;
-//   * K and V are streamed once, in one pass: the P.V accumulation uses an
-//     online (running-max) softmax per 16-lane group, rescaled when combined;
-//   * the logit of every slot is kept in fp64 and staged in LDS.  The score
-//     bookkeeping (softmax denominator, a += p, abar, arg-min, merge weights)
-//     is done in fp64 from that staged row after the streaming pass.  This
-//     costs one extra convert per K element on a memory-bound kernel and makes
-//     the eviction decision reproduce an fp64 reference exactly (differences
-//     ~1e-15 relative in abar) instead of drifting apart after the first
-//     near-tie;
+//   * K and V are each streamed exactly once.  Phase 1 streams K and leaves the
+//     logit of every entry, in fp64, in LDS.  Phase 2 streams V and accumulates
+//     exp(logit - max) . V in fp32 (fp64 for an fp32 cache);
+//   * phase 2 is wave-specialised: wave 0 does the score bookkeeping of
+//     Algorithm 1 (softmax denominator, a += A_t, abar = a/n, arg-min, right
+//     neighbour, merge weights) from the staged logit row while the other waves
+//     stream V, so the dependent chain of the compression hides behind the
+//     second half of the memory traffic;
+//   * the bookkeeping is fp64 throughout.  That costs one extra convert per K
+//     element on a memory-bound kernel and makes the eviction decision reproduce
+//     an fp64 reference exactly (differences ~1e-15 relative in abar) instead of
+//     drifting apart after the first near-tie;
 //   * the path is a GEMV per unit with no reuse across units: no MFMA.
 //
-// Slot order in memory is not token order (see wkv_internal.h): the victim's
-// slot is reused for the next token, so compression moves no K/V row at all.
+// Slot order in memory is not token order (see wkv_internal.h): the incoming
+// token is attended straight from the caller's k_new/v_new buffers and then
+// written into the slot the victim vacates, so compression moves no K/V row.
+//
+// Latency matters as much as bandwidth here (one launch streams ~50 MB, ~7 us
+// at peak): everything the bookkeeping needs from memory (score sums, token
+// positions) is requested before the streaming loop starts, the workgroup meets
+// at two barriers only, and wave-level reductions use DPP row operations plus
+// v_readlane, not LDS permutes.
 #include "wkv_internal.h"
 
 #include <math.h>
@@ -148,39 +158,77 @@ template <class S> __device__ __forceinline__ S rescale(S m, S M) {
     return (m == neg_inf<S>()) ? (S)0 : soft_exp(m - M);
 }
 
-// --------------------------------------------------------- block reductions
-// red: LDS scratch of >= 16 doubles.  Results are identical in every thread and
-// do not depend on timing (fixed tree).
-__device__ __forceinline__ double block_max(double x, double* red, int tid, int nw) {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) x = fmax(x, __shfl_xor(x, o));
-    if ((tid & 63) == 0) red[tid >> 6] = x;
-    __syncthreads();
-    double r = red[0];
-    for (int w = 1; w < nw; ++w) r = fmax(r, red[w]);
-    __syncthreads();
-    return r;
+// ------------------------------------------------------- wave-level reductions
+// All 64 lanes active.  Results are uniform across the wave and depend only on
+// the data (fixed combination order), never on timing.
+__device__ __forceinline__ double readlane_f64(double x, int l) {
+    const int lo = __builtin_amdgcn_readlane(__double2loint(x), l);
+    const int hi = __builtin_amdgcn_readlane(__double2hiint(x), l);
+    return __hiloint2double(hi, lo);
 }
 
-__device__ __forceinline__ double block_sum(double x, double* red, int tid, int nw) {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) x += __shfl_xor(x, o);
-    if ((tid & 63) == 0) red[tid >> 6] = x;
-    __syncthreads();
-    double r = red[0];
-    for (int w = 1; w < nw; ++w) r += red[w];
-    __syncthreads();
-    return r;
+__device__ __forceinline__ double wave_sum(double x) {
+    x = row_allsum(x);
+    return ((readlane_f64(x, 0) + readlane_f64(x, 16)) + readlane_f64(x, 32)) + readlane_f64(x, 48);
 }
 
+__device__ __forceinline__ int wave_sum(int x) {
+    x = row_allsum(x);
+    return __builtin_amdgcn_readlane(x, 0) + __builtin_amdgcn_readlane(x, 16) +
+           __builtin_amdgcn_readlane(x, 32) + __builtin_amdgcn_readlane(x, 48);
+}
+
+// candidate victim: lexicographic (score, token index), so ties go to the oldest token
 struct Best { double s; int pos; int phys; };
 
-// lexicographic (score, token index): ties go to the oldest token
 __device__ __forceinline__ bool better(double s, int pos, const Best& b) {
     return (s < b.s) || (s == b.s && pos < b.pos);
 }
 
+template <int CTRL> __device__ __forceinline__ void best_step(Best& b) {
+    const Best o = { dpp<CTRL>(b.s), dpp<CTRL>(b.pos), dpp<CTRL>(b.phys) };
+    if (better(o.s, o.pos, b)) b = o;
+}
+
+__device__ __forceinline__ Best wave_argmin(Best b) {
+    best_step<0xB1>(b); best_step<0x4E>(b); best_step<0x141>(b); best_step<0x140>(b);
+    Best r = { readlane_f64(b.s, 0), __builtin_amdgcn_readlane(b.pos, 0), __builtin_amdgcn_readlane(b.phys, 0) };
+#pragma unroll
+    for (int l = 16; l < 64; l += 16) {
+        const Best o = { readlane_f64(b.s, l), __builtin_amdgcn_readlane(b.pos, l),
+                         __builtin_amdgcn_readlane(b.phys, l) };
+        if (better(o.s, o.pos, r)) r = o;
+    }
+    return r;
+}
+
+// right-hand neighbour of the victim: the live entry with the smallest token
+// index above the victim's (token indices are unique), with its slot and score
+struct Next { int pos; int phys; double s; };
+
+template <int CTRL> __device__ __forceinline__ void next_step(Next& n) {
+    const Next o = { dpp<CTRL>(n.pos), dpp<CTRL>(n.phys), dpp<CTRL>(n.s) };
+    if (o.pos < n.pos) n = o;
+}
+
+__device__ __forceinline__ Next wave_next(Next n) {
+    next_step<0xB1>(n); next_step<0x4E>(n); next_step<0x141>(n); next_step<0x140>(n);
+    Next r = { __builtin_amdgcn_readlane(n.pos, 0), __builtin_amdgcn_readlane(n.phys, 0), readlane_f64(n.s, 0) };
+#pragma unroll
+    for (int l = 16; l < 64; l += 16) {
+        const Next o = { __builtin_amdgcn_readlane(n.pos, l), __builtin_amdgcn_readlane(n.phys, l),
+                         readlane_f64(n.s, l) };
+        if (o.pos < r.pos) r = o;
+    }
+    return r;
+}
+
+constexpr int MAXPT = 4;       // entries whose a/pos one thread fetches ahead of the streaming loop
+constexpr int NONE_POS = 0x7FFFFFFF;
+
 // ------------------------------------------------------------------ the kernel
+// Entries attended in step t: the Lc = min(t, m) cached slots, then the incoming
+// token as entry Lc (its row is read from k_new / v_new).  L = Lc + 1.
 template <class TT, int D, int U>
 __global__ __launch_bounds__(1024)
 void wkv_step_kernel(WkvCache c, const void* __restrict__ q_, const void* __restrict__ k_,
@@ -191,32 +239,52 @@ void wkv_step_kernel(WkvCache c, const void* __restrict__ q_, const void* __rest
     constexpr int NW32 = EPL * TT::BYTES / 4;    // 32-bit words per lane per row
     constexpr int ROWB = D * TT::BYTES;          // bytes per row
     constexpr int LANEB = EPL * TT::BYTES;       // bytes per lane per row
+    constexpr int EPW  = (D + 63) / 64;          // row elements per lane of the bookkeeping wave
 
     const int tid = threadIdx.x, NT = blockDim.x;
     const int NG = NT >> 4, gid = tid >> 4, sub = tid & 15;
     const int NW = NT >> 6, wid = tid >> 6, lane = tid & 63;
     const int u = blockIdx.x;
-    const int cap = c.cap;
-    const int L = (t + 1 < cap) ? t + 1 : cap;            // slots attended this step
-    const bool compress = t >= c.m;                        // cache exceeds m after the append
-    const int f = (t < c.m) ? t : c.free_slot[u];          // slot of the incoming token
+    const int m = c.m;
+    const int Lc = (t < m) ? t : m;                        // cached entries
+    const int L = Lc + 1;                                  // entries attended
+    const bool compress = t >= m;                          // the cache would exceed m
 
     // ---- LDS carve-up
     extern __shared__ double lds[];
-    double* sl   = lds;                                    // [cap] logit -> exp -> score
-    double* red  = sl + cap;                               // [32] reduction scratch
-    S*      part = reinterpret_cast<S*>(red + 32);         // [NW][D] per-wave P.V partials
-    S*      pm   = part + NW * D;                          // [16] per-wave running max
-    S*      plw  = pm + 16;                                // [16] per-wave denominator
-    int*    pl   = reinterpret_cast<int*>(plw + 16);       // [cap] token index of each slot
-    int*    redi = pl + cap;                               // [64] integer reduction scratch
+    double* sl   = lds;                                    // [m+1] fp64 logit of every entry
+    double* al   = sl + m + 1;                             // [m+1] score sums a
+    double* wmax = al + m + 1;                             // [16] per-wave maximum logit
+    S*      part = reinterpret_cast<S*>(wmax + 16);        // [NW][D] per-wave P.V partials
+    S*      plw  = part + NW * D;                          // [16] per-wave sum of weights
+    int*    pl   = reinterpret_cast<int*>(plw + 16);       // [m+1] token index of every entry
 
-    const char* Kc = reinterpret_cast<const char*>(c.K) + (size_t)u * cap * ROWB;
-    char*       Kw = reinterpret_cast<char*>(c.K) + (size_t)u * cap * ROWB;
-    char*       Vc = reinterpret_cast<char*>(c.V) + (size_t)u * cap * ROWB;
+    char*       Kc = reinterpret_cast<char*>(c.K) + (size_t)u * m * ROWB;
+    char*       Vc = reinterpret_cast<char*>(c.V) + (size_t)u * m * ROWB;
     const char* qu = reinterpret_cast<const char*>(q_) + (size_t)u * ROWB;
     const char* ku = reinterpret_cast<const char*>(k_) + (size_t)u * ROWB;
     const char* vu = reinterpret_cast<const char*>(v_) + (size_t)u * ROWB;
+    double*  au = c.a + (size_t)u * m;
+    int32_t* pu = c.pos + (size_t)u * m;
+
+    // ---- everything the bookkeeping needs from memory, requested before the streaming loop
+    double a_reg[MAXPT];
+    int pos_reg[MAXPT];
+#pragma unroll
+    for (int k = 0; k < MAXPT; ++k) {
+        const int i = tid + k * NT;
+        a_reg[k] = (i < Lc) ? au[i] : 0.0;                 // a = [a, 0]
+        pos_reg[k] = (i < Lc) ? pu[i] : ((i == Lc) ? t : NONE_POS);
+    }
+    float knew_e[EPW], vnew_e[EPW];                        // the incoming row, for wave 0's write-back
+    if (wid == 0) {
+#pragma unroll
+        for (int e = 0; e < EPW; ++e) {
+            const int col = lane + 64 * e;
+            knew_e[e] = (col < D) ? load_elem<TT>(ku, col) : 0.f;
+            vnew_e[e] = (col < D) ? load_elem<TT>(vu, col) : 0.f;
+        }
+    }
 
     // ---- the query, pre-scaled by 1/sqrt(d), in fp64
     double qd[EPL];
@@ -229,27 +297,17 @@ void wkv_step_kernel(WkvCache c, const void* __restrict__ q_, const void* __rest
         for (int e = 0; e < EPL; ++e) qd[e] = (double)x[e] * scale;
     }
 
-    // ---- streaming pass over the L slots: logits (fp64, to LDS) and online softmax . V
-    S m_run = neg_inf<S>(), l_run = (S)0;
-    S acc[EPL];
-#pragma unroll
-    for (int e = 0; e < EPL; ++e) acc[e] = (S)0;
-
+    // ---- phase 1: stream K, logits in fp64 to LDS
+    double mx = -INFINITY;
     for (int base = gid; base < L; base += NG * U) {
-        uint32_t kw[U][NW32], vw[U][NW32];
-        bool valid[U];
+        uint32_t kw[U][NW32];
 #pragma unroll
         for (int uu = 0; uu < U; ++uu) {
             int i = base + uu * NG;
-            valid[uu] = i < L;
-            if (!valid[uu]) i = base;                       // harmless duplicate load
-            const char* kp = (i == f) ? ku : Kc + (size_t)i * ROWB;
-            const char* vp = (i == f) ? vu : Vc + (size_t)i * ROWB;
+            if (i >= L) i = base;                           // harmless duplicate load
+            const char* kp = (i == Lc) ? ku : Kc + (size_t)i * ROWB;
             load_words<NW32>(kp + sub * LANEB, kw[uu]);
-            load_words<NW32>(vp + sub * LANEB, vw[uu]);
         }
-        S sv[U];
-        S mnew = m_run;
 #pragma unroll
         for (int uu = 0; uu < U; ++uu) {
             const int i = base + uu * NG;
@@ -259,160 +317,176 @@ void wkv_step_kernel(WkvCache c, const void* __restrict__ q_, const void* __rest
 #pragma unroll
             for (int e = 0; e < EPL; ++e) dot = fma((double)kx[e], qd[e], dot);
             dot = row_allsum(dot);
-            if (valid[uu]) {
+            if (i < L) {
                 if (sub == 0) sl[i] = dot;
-                if (i == f) store_words<NW32>(Kw + (size_t)f * ROWB + sub * LANEB, kw[uu]);   // append k_t
+                mx = fmax(mx, dot);
             }
-            sv[uu] = valid[uu] ? (S)dot : neg_inf<S>();
-            mnew = (sv[uu] > mnew) ? sv[uu] : mnew;
-        }
-        const S sc = rescale(m_run, mnew);
-        l_run *= sc;
-#pragma unroll
-        for (int e = 0; e < EPL; ++e) acc[e] *= sc;
-#pragma unroll
-        for (int uu = 0; uu < U; ++uu) {
-            const S p = rescale(sv[uu], mnew);
-            float vx[EPL];
-            decode<TT, EPL, NW32>(vw[uu], vx);
-            l_run += p;
-#pragma unroll
-            for (int e = 0; e < EPL; ++e) acc[e] += p * (S)vx[e];
-        }
-        m_run = mnew;
-    }
-
-    // ---- combine the four 16-lane groups of each wave, then the waves
-#pragma unroll
-    for (int off = 16; off <= 32; off <<= 1) {
-        const S mo = __shfl_xor(m_run, off), lo = __shfl_xor(l_run, off);
-        const S M = (mo > m_run) ? mo : m_run;
-        const S sa = rescale(m_run, M), sb = rescale(mo, M);
-        l_run = l_run * sa + lo * sb;
-#pragma unroll
-        for (int e = 0; e < EPL; ++e) acc[e] = acc[e] * sa + __shfl_xor(acc[e], off) * sb;
-        m_run = M;
-    }
-    if (lane < ROW_LANES) {
-#pragma unroll
-        for (int e = 0; e < EPL; ++e) part[wid * D + lane * EPL + e] = acc[e];
-        if (lane == 0) { pm[wid] = m_run; plw[wid] = l_run; }
-    }
-    __syncthreads();     // also publishes sl[0..L)
-
-    if (tid < D) {       // o_t = A_t^T V_t   (Section III-A)
-        S M = pm[0];
-        for (int w = 1; w < NW; ++w) M = (pm[w] > M) ? pm[w] : M;
-        S num = (S)0, den = (S)0;
-        for (int w = 0; w < NW; ++w) {
-            const S sc = rescale(pm[w], M);
-            num += part[w * D + tid] * sc;
-            den += plw[w] * sc;
-        }
-        const S o = num / den;
-        if constexpr (TT::BYTES == 4) reinterpret_cast<float*>(out_)[(size_t)u * D + tid] = (float)o;
-        else store_elem<TT>(out_, (size_t)u * D + tid, (float)o);
-    }
-
-    // ---- score bookkeeping in fp64 from the staged logit row
-    double mx = -INFINITY;
-    for (int i = tid; i < L; i += NT) mx = fmax(mx, sl[i]);
-    mx = block_max(mx, red, tid, NW);
-    double part_sum = 0.0;
-    for (int i = tid; i < L; i += NT) { const double e = exp(sl[i] - mx); sl[i] = e; part_sum += e; }
-    const double denom = block_sum(part_sum, red, tid, NW);
-
-    double*  au = c.a + (size_t)u * cap;
-    int32_t* pu = c.pos + (size_t)u * cap;
-    Best best = { INFINITY, 0x7FFFFFFF, -1 };
-    int nonfinite = 0;
-    for (int i = tid; i < L; i += NT) {
-        const double p = sl[i] / denom;                          // A_t[i]
-        const double ai = ((i == f) ? 0.0 : au[i]) + p;          // a = [a, 0] + A_t
-        au[i] = ai;
-        const int pi = (i == f) ? t : pu[i];
-        pl[i] = pi;
-        if (compress) {
-            const double ni = (double)(t - pi + 1);              // n = steps this token has been attended
-            double score = (c.score_mode == 0) ? ai / ni : (c.score_mode == 1) ? ai : p;
-            if (!(score == score) || score == INFINITY) { score = INFINITY; nonfinite = 1; }
-            sl[i] = score;
-            if (pi <= t - c.R && pi >= c.n_sink && better(score, pi, best)) best = { score, pi, i };
         }
     }
-    if (tid == 0) pu[f] = t;
-
-    int ev_pos = -1, ev_rank = -1;
-    if (compress) {      // uniform over the workgroup
-        // arg-min over the workgroup
+    // mx is uniform within each 16-lane row: combine the four rows of the wave
+    mx = fmax(fmax(readlane_f64(mx, 0), readlane_f64(mx, 16)), fmax(readlane_f64(mx, 32), readlane_f64(mx, 48)));
+    if (lane == 0) wmax[wid] = mx;
 #pragma unroll
-        for (int o = 32; o > 0; o >>= 1) {
-            Best b2 = { __shfl_xor(best.s, o), __shfl_xor(best.pos, o), __shfl_xor(best.phys, o) };
-            if (better(b2.s, b2.pos, best)) best = b2;
-        }
-        if (lane == 0) { red[wid] = best.s; redi[wid] = best.pos; redi[16 + wid] = best.phys; }
-        __syncthreads();   // also publishes pl[] and the scores in sl[]
-        best = { red[0], redi[0], redi[16] };
-        for (int w = 1; w < NW; ++w)
-            if (better(red[w], redi[w], best)) best = { red[w], redi[w], redi[16 + w] };
-        __syncthreads();
-        const int j = best.phys, pj = best.pos;
+    for (int k = 0; k < MAXPT; ++k) {
+        const int i = tid + k * NT;
+        if (i < L) { al[i] = a_reg[k]; pl[i] = pos_reg[k]; }
+    }
+    __syncthreads();     // barrier 1: logits, score sums and token indices are staged
 
-        // right-hand neighbour in token order and the victim's rank
-        int rpos = 0x7FFFFFFF, rphys = -1, cnt = 0;
-        for (int i = tid; i < L; i += NT) {
-            const int pi = pl[i];
-            if (pi < pj) ++cnt;
-            else if (pi > pj && pi < rpos) { rpos = pi; rphys = i; }
-        }
+    double Mx = wmax[0];
+    for (int w = 1; w < NW; ++w) Mx = fmax(Mx, wmax[w]);
+
+    // state wave 0 carries across barrier 2
+    int dest = t;        // slot that receives the incoming token (fill phase: the next free one)
+    int ev_pos = -1, ev_rank = -1, j = -1, r = -1;
+    double merged[EPW];
+    bool zero_den = false;
+
+    if (wid != 0) {
+        // ---- phase 2, waves 1..NW-1: stream V, accumulate exp(logit - max) . V
+        const int g2 = gid - 4, NG2 = NG - 4;
+        S l_run = (S)0;
+        S acc[EPL];
 #pragma unroll
-        for (int o = 32; o > 0; o >>= 1) {
-            const int rp2 = __shfl_xor(rpos, o), rh2 = __shfl_xor(rphys, o);
-            if (rp2 < rpos) { rpos = rp2; rphys = rh2; }
-            cnt += __shfl_xor(cnt, o);
-        }
-        if (lane == 0) { redi[wid] = rpos; redi[16 + wid] = rphys; redi[32 + wid] = cnt; }
-        __syncthreads();
-        rpos = redi[0]; rphys = redi[16]; cnt = redi[32];
-        for (int w = 1; w < NW; ++w) {
-            if (redi[w] < rpos) { rpos = redi[w]; rphys = redi[16 + w]; }
-            cnt += redi[32 + w];
-        }
-        const int r = rphys;
-        ev_pos = pj; ev_rank = cnt;
-        // A candidate and a right neighbour always exist (n_sink + R <= m, and the
-        // incoming token is newer than any candidate).  Should the cache ever be
-        // inconsistent, touch nothing out of range and flag it.
-        const bool sane = j >= 0 && r >= 0;
-        if (!sane && tid == 0) atomicAdd(&c.status[1], 1);
-
-        if (tid < D && sane) {
-            if (c.merge_mode == 0) {
-                // V[r] <- (abar_j V[j] + abar_r V[r]) / (abar_j + abar_r)     (Algorithm 1, Section IV)
-                const double wj = sl[j], wr = sl[r];
-                const double den = wj + wr;
-                const double vj = (double)load_elem<TT>(Vc + (size_t)j * ROWB, tid);
-                const double vr = (double)((r == f) ? load_elem<TT>(vu, tid)
-                                                    : load_elem<TT>(Vc + (size_t)r * ROWB, tid));
-                const double x = (den > 0.0) ? (wj * vj + wr * vr) / den : 0.5 * vj + 0.5 * vr;
-                store_elem_f64<TT>(Vc + (size_t)r * ROWB, tid, x);
-                if (tid == 0 && !(den > 0.0)) atomicAdd(&c.status[0], 1);
+        for (int e = 0; e < EPL; ++e) acc[e] = (S)0;
+        for (int base = g2; base < L; base += NG2 * U) {
+            uint32_t vw[U][NW32];
+#pragma unroll
+            for (int uu = 0; uu < U; ++uu) {
+                int i = base + uu * NG2;
+                if (i >= L) i = base;
+                const char* vp = (i == Lc) ? vu : Vc + (size_t)i * ROWB;
+                load_words<NW32>(vp + sub * LANEB, vw[uu]);
             }
-            if (r != f || c.merge_mode != 0)                                   // append v_t
-                store_elem<TT>(Vc + (size_t)f * ROWB, tid, load_elem<TT>(vu, tid));
+#pragma unroll
+            for (int uu = 0; uu < U; ++uu) {
+                const int i = base + uu * NG2;
+                const S p = (i < L) ? soft_exp((S)(sl[(i < L) ? i : base] - Mx)) : (S)0;
+                float vx[EPL];
+                decode<TT, EPL, NW32>(vw[uu], vx);
+                l_run += p;
+#pragma unroll
+                for (int e = 0; e < EPL; ++e) acc[e] += p * (S)vx[e];
+            }
         }
-        if (tid == 0 && sane) {
-            int32_t* nm = c.nmerged + (size_t)u * cap;
-            const int nm_r = (r == f) ? 1 : nm[r];
-            if (c.merge_mode == 0) nm[r] = nm_r + nm[j]; else if (r == f) nm[r] = 1;
-            if (r != f) nm[f] = 1;
-            c.free_slot[u] = j;
+#pragma unroll
+        for (int off = 16; off <= 32; off <<= 1) {
+            l_run += __shfl_xor(l_run, off);
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) acc[e] += __shfl_xor(acc[e], off);
+        }
+        if (lane < ROW_LANES) {
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) part[wid * D + lane * EPL + e] = acc[e];
+            if (lane == 0) plw[wid] = l_run;
         }
     } else {
-        if (tid < D) store_elem<TT>(Vc + (size_t)f * ROWB, tid, load_elem<TT>(vu, tid));     // append v_t
-        if (tid == 0) c.nmerged[(size_t)u * cap + f] = 1;
+        // ---- phase 2, wave 0: the bookkeeping of Algorithm 1, in fp64, from LDS
+        double psum = 0.0;
+        for (int i = lane; i < L; i += 64) psum += exp(sl[i] - Mx);
+        const double denom = wave_sum(psum);
+
+        Best best = { INFINITY, NONE_POS, -1 };
+        int nonfinite = 0;
+        for (int i = lane; i < L; i += 64) {
+            const double p = exp(sl[i] - Mx) / denom;                // A_t[i]
+            const double ai = al[i] + p;                             // a = [a, 0] + A_t
+            al[i] = ai;
+            if (compress) {
+                const int pi = pl[i];
+                const double ni = (double)(t - pi + 1);              // n: steps this token has been attended
+                double score = (c.score_mode == 0) ? ai / ni : (c.score_mode == 1) ? ai : p;
+                if (!(score == score) || score == INFINITY) { score = INFINITY; nonfinite = 1; }
+                if (pi <= t - c.R && pi >= c.n_sink && better(score, pi, best)) best = { score, pi, i };
+            }
+        }
+        if (nonfinite) atomicAdd(&c.status[1], 1);
+
+        if (compress) {
+            best = wave_argmin(best);
+            j = best.phys;
+            const int pj = best.pos;
+            Next nx = { NONE_POS, -1, 0.0 };
+            int cnt = 0;
+            for (int i = lane; i < L; i += 64) {
+                const int pi = pl[i];
+                if (pi < pj) ++cnt;
+                else if (pi > pj && pi < nx.pos) nx = { pi, i, 0.0 };
+            }
+            nx = wave_next(nx);
+            cnt = wave_sum(cnt);
+            r = nx.phys;
+            ev_pos = pj; ev_rank = cnt;
+            // A candidate and a right neighbour always exist (n_sink + R <= m, and the
+            // incoming token is newer than any candidate).  Should the cache ever be
+            // inconsistent, touch nothing out of range and flag it.
+            if (j < 0 || r < 0) {
+                if (lane == 0) atomicAdd(&c.status[1], 1);
+                j = r = -1;
+            } else {
+                dest = j;
+            }
+        }
+        // score sums back to memory: every entry but the victim; the incoming token's goes to its slot
+        for (int i = lane; i < Lc; i += 64)
+            if (i != j) au[i] = al[i];
+        if (lane == 0 && (!compress || j >= 0)) { au[dest] = al[Lc]; pu[dest] = t; }
+
+        if (compress && j >= 0 && c.merge_mode == 0) {
+            // V[r] <- (abar_j V[j] + abar_r V[r]) / (abar_j + abar_r)     (Algorithm 1, Section IV)
+            const double sj = best.s;
+            const double sr = al[r] / (double)(t - pl[r] + 1);
+            const double den = sj + sr;
+            zero_den = !(den > 0.0);
+#pragma unroll
+            for (int e = 0; e < EPW; ++e) {
+                const int col = lane + 64 * e;
+                if (col < D) {
+                    const double vj = (double)load_elem<TT>(Vc + (size_t)j * ROWB, col);
+                    const double vr = (double)((r == Lc) ? vnew_e[e] : load_elem<TT>(Vc + (size_t)r * ROWB, col));
+                    merged[e] = zero_den ? 0.5 * vj + 0.5 * vr : (sj * vj + sr * vr) / den;
+                }
+            }
+        }
     }
-    if (nonfinite) atomicAdd(&c.status[1], 1);
+    __syncthreads();     // barrier 2: every V row has been read, partials are staged
+
+    if (tid < D) {       // o_t = A_t^T V_t   (Section III-A)
+        const int col = tid;
+        S num = (S)0, den = (S)0;
+        for (int w = 1; w < NW; ++w) { num += part[w * D + col]; den += plw[w]; }
+        const S o = num / den;
+        if constexpr (TT::BYTES == 4) reinterpret_cast<float*>(out_)[(size_t)u * D + col] = (float)o;
+        else store_elem<TT>(out_, (size_t)u * D + col, (float)o);
+    }
+    if (wid == 0 && (!compress || j >= 0)) {
+        // ---- write-back of the rows: merged value, then the incoming token into its slot
+        const bool merge = compress && c.merge_mode == 0;
+#pragma unroll
+        for (int e = 0; e < EPW; ++e) {
+            const int col = lane + 64 * e;
+            if (col < D) {
+                if (merge && r == Lc) {
+                    store_elem_f64<TT>(Vc + (size_t)dest * ROWB, col, merged[e]);   // folded straight into the new token
+                } else {
+                    if (merge) store_elem_f64<TT>(Vc + (size_t)r * ROWB, col, merged[e]);
+                    store_elem<TT>(Vc + (size_t)dest * ROWB, col, vnew_e[e]);
+                }
+                store_elem<TT>(Kc + (size_t)dest * ROWB, col, knew_e[e]);
+            }
+        }
+        if (lane == 0) {
+            int32_t* nm = c.nmerged + (size_t)u * m;
+            if (merge) {
+                const int nj = nm[j];
+                if (r == Lc) nm[dest] = 1 + nj;
+                else { nm[r] += nj; nm[dest] = 1; }
+                if (zero_den) atomicAdd(&c.status[0], 1);
+            } else {
+                nm[dest] = 1;
+            }
+        }
+    }
     if (tid == 0) {
         const size_t row = (size_t)(t % c.log_cap) * c.units + u;
         c.log_pos[row] = ev_pos;
@@ -424,25 +498,27 @@ template <class TT, int D>
 hipError_t launch(const WkvCache& c, int threads, size_t lds, const void* q, const void* k,
                   const void* v, void* out, int t, hipStream_t stream)
 {
-    hipLaunchKernelGGL((wkv_step_kernel<TT, D, 2>), dim3(c.units), dim3(threads), lds, stream,
+    hipLaunchKernelGGL((wkv_step_kernel<TT, D, 4>), dim3(c.units), dim3(threads), lds, stream,
                        c, q, k, v, out, t);
     return hipGetLastError();
 }
 
 }  // namespace
 
-size_t wkv_step_lds_bytes(int cap, int dtype, int head_dim, int threads)
+size_t wkv_step_lds_bytes(int m, int dtype, int head_dim, int threads)
 {
     const size_t s = (dtype == 0) ? 8 : 4;     // sizeof(soft_t)
     const size_t nw = (size_t)threads / 64;
-    return (size_t)cap * 8 + 32 * 8 + (nw * (size_t)head_dim + 32) * s + (size_t)cap * 4 + 64 * 4;
+    return ((size_t)m + 1) * 20 + 16 * 8 + (nw * (size_t)head_dim + 16) * s;
 }
+
+int wkv_step_max_entries(int threads) { return MAXPT * threads; }
 
 hipError_t wkv_launch_step(const WkvCache& c, int dtype, int head_dim, int threads,
                            const void* q, const void* k_new, const void* v_new, void* out,
                            int64_t t, hipStream_t stream)
 {
-    const size_t lds = wkv_step_lds_bytes(c.cap, dtype, head_dim, threads);
+    const size_t lds = wkv_step_lds_bytes(c.m, dtype, head_dim, threads);
     const int ti = (int)t;
 #define WKV_CASE(DT, TT, DD) \
     if (dtype == DT && head_dim == DD) return launch<TT, DD>(c, threads, lds, q, k_new, v_new, out, ti, stream);
