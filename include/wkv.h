@@ -141,9 +141,9 @@ const char* wkv_last_error(void);
 size_t wkv_workspace_bytes(const wkv_options* opt);
 
 /* Algorithmic HBM bytes one wkv_step moves in steady state (cache full): per
- * unit (budget+1) K rows and V rows read, score sum read+written, position
- * read, q/k_new/v_new read, out written, the new K/V rows written, two V rows
- * read and one written by the merge.  Host-only arithmetic. */
+ * unit (budget+1) K rows and V rows read, score sum read+written, token index
+ * read, q/k_new/v_new read, out written, the new K/V rows written, the merged
+ * V row written.  Host-only arithmetic. */
 size_t wkv_step_bytes(const wkv_options* opt);
 
 int wkv_version(void);

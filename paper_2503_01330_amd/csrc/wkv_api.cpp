@@ -30,7 +30,7 @@ int fail(int code, const char* fmt, ...)
 
 int dtype_bytes(int dtype) { return dtype == WKV_FP32 ? 4 : 2; }
 
-constexpr size_t LDS_LIMIT = 64 * 1024;
+constexpr size_t LDS_LIMIT = 160 * 1024;    // LDS per compute unit on gfx950
 
 // Returns 0 and fills *threads, or a negative code with the reason in g_err.
 int validate(const wkv_options& o, int* threads)
@@ -83,7 +83,7 @@ Sizes sizes(const wkv_options& o)
     s.i32 = units * cap * sizeof(int32_t);
     s.log = logc * units * sizeof(int32_t);
     s.status = 2 * sizeof(int32_t);
-    s.total = 2 * s.kv + s.a + 2 * s.i32 + 2 * s.log + s.status;
+    s.total = 2 * s.kv + s.a + 3 * s.i32 + 2 * s.log + s.status;
     return s;
 }
 
@@ -115,10 +115,12 @@ size_t wkv_step_bytes(const wkv_options* opt)
     if (!opt || validate(*opt, &th) != WKV_OK) return 0;
     const size_t units = (size_t)opt->batch * opt->heads, L = (size_t)opt->budget + 1;
     const size_t row = (size_t)opt->head_dim * dtype_bytes(opt->dtype);
-    // per attended entry: K row + V row + score sum read and written (fp64) + position read
-    // per unit: q, k_new, v_new in, out out, K/V rows of the new token written,
-    //           merge reads two V rows and writes one
-    return units * (L * (2 * row + 16 + 4) + 4 * row + 2 * row + 3 * row);
+    // What the method itself has to move (implementation extras such as the next-token
+    // links are left out):
+    //   per attended entry: K row + V row + score sum read and written (fp64) + token index read
+    //   per unit: q, k_new, v_new in, out out; the new token's K and V rows written;
+    //             the merged V row written (its two inputs are among the rows already read)
+    return units * (L * (2 * row + 16 + 4) + 4 * row + 2 * row + 1 * row);
 }
 
 int wkv_create_ex(wkv_handle** hp, const wkv_options* opt)
@@ -138,6 +140,21 @@ int wkv_create_ex(wkv_handle** hp, const wkv_options* opt)
         delete h;
         return fail(WKV_EHIP, "hipGetDevice: %s", hipGetErrorString(e));
     }
+    {
+        int lds_max = 0;
+        const size_t lds = wkv_step_lds_bytes(opt->budget, opt->dtype, opt->head_dim, threads);
+        e = hipDeviceGetAttribute(&lds_max, hipDeviceAttributeMaxSharedMemoryPerBlock, h->device);
+        if (e == hipSuccess && lds > (size_t)lds_max) {
+            delete h;
+            return fail(WKV_ESIZE, "a score row of %d entries needs %zu bytes of LDS, the device offers %d",
+                        opt->budget + 1, lds, lds_max);
+        }
+        if (e == hipSuccess) e = wkv_step_prepare(opt->dtype, opt->head_dim, lds);
+        if (e != hipSuccess) {
+            delete h;
+            return fail(WKV_EHIP, "preparing the kernel: %s", hipGetErrorString(e));
+        }
+    }
     const Sizes s = sizes(h->opt);
     WkvCache& c = h->c;
     memset(&c, 0, sizeof c);
@@ -147,7 +164,7 @@ int wkv_create_ex(wkv_handle** hp, const wkv_options* opt)
 
     struct { void** p; size_t n; int fill; } bufs[] = {
         { &c.K, s.kv, 0 }, { &c.V, s.kv, 0 }, { (void**)&c.a, s.a, 0 },
-        { (void**)&c.pos, s.i32, 0xFF }, { (void**)&c.nmerged, s.i32, 0 },
+        { (void**)&c.pos, s.i32, 0xFF }, { (void**)&c.nxt, s.i32, 0xFF }, { (void**)&c.nmerged, s.i32, 0 },
         { (void**)&c.log_pos, s.log, 0xFF },
         { (void**)&c.log_slot, s.log, 0xFF }, { (void**)&c.status, s.status, 0 },
     };
@@ -295,7 +312,7 @@ int wkv_destroy(wkv_handle* h)
     if (!h) return WKV_OK;
     (void)hipDeviceSynchronize();
     WkvCache& c = h->c;
-    void* bufs[] = { c.K, c.V, c.a, c.pos, c.nmerged, c.log_pos, c.log_slot, c.status };
+    void* bufs[] = { c.K, c.V, c.a, c.pos, c.nxt, c.nmerged, c.log_pos, c.log_slot, c.status };
     for (void* b : bufs) if (b) (void)hipFree(b);
     delete h;
     return WKV_OK;

@@ -16,13 +16,14 @@
 //
 // Physical slot order is therefore NOT token order.  Attention is a sum over
 // slots, so any order gives the same result; token order -- needed only to find
-// the right-hand neighbour of the victim -- is carried by pos[].  No row of K or
-// V is ever moved.
+// the right-hand neighbour of the victim -- is carried by pos[] (for readback) and
+// by the linked list nxt[] (for the kernel).  No row of K or V is ever moved.
 struct WkvCache {
     void*    K;          // [units][m][D] storage dtype; a row is written once per token it holds
     void*    V;          // [units][m][D] storage dtype; one row rewritten per compression
     double*  a;          // [units][m] accumulated attention weight (Algorithm 1's list a), fp64
     int32_t* pos;        // [units][m] original token index of the slot's key
+    int32_t* nxt;        // [units][m] slot of the next token in token order, -1 for the newest
     int32_t* nmerged;    // [units][m] raw values folded into the slot
     int32_t* log_pos;    // [log_cap][units] evicted token index per step (ring), -1 = none
     int32_t* log_slot;   // [log_cap][units] its rank in token order
@@ -39,6 +40,9 @@ hipError_t wkv_launch_step(const WkvCache& c, int dtype, int head_dim, int threa
 
 // Bytes of dynamic LDS wkv_launch_step needs for this shape.
 size_t wkv_step_lds_bytes(int m, int dtype, int head_dim, int threads);
+
+// Raises the kernel's dynamic-LDS limit to `lds` bytes (needed above 64 KiB).
+hipError_t wkv_step_prepare(int dtype, int head_dim, size_t lds);
 
 // Largest number of attended entries (m + 1) a workgroup of this size handles.
 int wkv_step_max_entries(int threads);

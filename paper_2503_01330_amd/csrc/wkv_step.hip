@@ -12,18 +12,16 @@
 //     for d=128 half precision) fully coalesced, and the 16-lane dot-product
 //     reduction is four DPP steps (quad_perm, quad_perm, row_half_mirror,
 //     row_mirror) with no LDS traffic;
-//   * K and V are each streamed exactly once.  Phase 1 streams K and leaves the
-//     logit of every entry, in fp64, in LDS.  Phase 2 streams V and accumulates
-//     exp(logit - max) . V in fp32 (fp64 for an fp32 cache);
-//   * phase 2 is wave-specialised: wave 0 does the score bookkeeping of
-//     Algorithm 1 (softmax denominator, a += A_t, abar = a/n, arg-min, right
-//     neighbour, merge weights) from the staged logit row while the other waves
-//     stream V, so the dependent chain of the compression hides behind the
-//     second half of the memory traffic;
-//   * the bookkeeping is fp64 throughout.  That costs one extra convert per K
-//     element on a memory-bound kernel and makes the eviction decision reproduce
-//     an fp64 reference exactly (differences ~1e-15 relative in abar) instead of
-//     drifting apart after the first near-tie;
+//   * K and V are each streamed exactly once, in one pass.  The logit of every
+//     entry is kept in fp64 and staged in LDS; exp(logit - running max) . V is
+//     accumulated in fp32 (fp64 for an fp32 cache) with an online softmax per
+//     16-lane group and rescaled when the groups are combined;
+//   * the score bookkeeping of Algorithm 1 (softmax denominator, a += A_t,
+//     abar = a/n, arg-min, right neighbour, merge weights) is fp64 throughout,
+//     computed from the staged logit row after the streaming pass.  That costs
+//     one extra convert per K element on a memory-bound kernel and makes the
+//     eviction decision reproduce an fp64 reference exactly (differences ~1e-15
+//     relative in abar) instead of drifting apart after the first near-tie;
 //   * the path is a GEMV per unit with no reuse across units: no MFMA.
 //
 // Slot order in memory is not token order (see wkv_internal.h): the incoming
@@ -32,12 +30,18 @@
 //
 // Latency matters as much as bandwidth here (one launch streams ~50 MB, ~7 us
 // at peak): everything the bookkeeping needs from memory (score sums, token
-// positions) is requested before the streaming loop starts, the workgroup meets
-// at two barriers only, and wave-level reductions use DPP row operations plus
-// v_readlane, not LDS permutes.
+// indices, links) is requested before the streaming loop starts, wave-level
+// reductions use DPP row operations plus v_readlane instead of LDS permutes,
+// per-wave results are combined by one DPP row reduction per wave, and the two
+// V rows of the merge are taken from the registers they were streamed into.
 #include "wkv_internal.h"
 
 #include <math.h>
+
+// Phase markers for an out-of-tree timing harness; they compile to nothing in the library.
+#ifndef WKV_MARK
+#define WKV_MARK(k)
+#endif
 
 namespace {
 
@@ -101,6 +105,21 @@ template <class TT> __device__ __forceinline__ float load_elem(const void* base,
     if constexpr (TT::BYTES == 4) return reinterpret_cast<const float*>(base)[idx];
     else if constexpr (__is_same(TT, TF16)) return (float)reinterpret_cast<const _Float16*>(base)[idx];
     else return __builtin_bit_cast(float, (uint32_t)reinterpret_cast<const uint16_t*>(base)[idx] << 16);
+}
+
+// one storage element as raw bits (no conversion: nothing waits on the load) and back
+template <class TT> __device__ __forceinline__ uint32_t load_bits(const void* base, int idx) {
+    if constexpr (TT::BYTES == 4) return reinterpret_cast<const uint32_t*>(base)[idx];
+    else return reinterpret_cast<const uint16_t*>(base)[idx];
+}
+template <class TT> __device__ __forceinline__ void store_bits(void* base, int idx, uint32_t b) {
+    if constexpr (TT::BYTES == 4) reinterpret_cast<uint32_t*>(base)[idx] = b;
+    else reinterpret_cast<uint16_t*>(base)[idx] = (uint16_t)b;
+}
+template <class TT> __device__ __forceinline__ float bits_to_f32(uint32_t b) {
+    if constexpr (TT::BYTES == 4) return __builtin_bit_cast(float, b);
+    else if constexpr (__is_same(TT, TF16)) return (float)__builtin_bit_cast(_Float16, (uint16_t)b);
+    else return __builtin_bit_cast(float, b << 16);
 }
 
 __device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
@@ -202,25 +221,25 @@ __device__ __forceinline__ Best wave_argmin(Best b) {
     return r;
 }
 
-// right-hand neighbour of the victim: the live entry with the smallest token
-// index above the victim's (token indices are unique), with its slot and score
-struct Next { int pos; int phys; double s; };
-
-template <int CTRL> __device__ __forceinline__ void next_step(Next& n) {
-    const Next o = { dpp<CTRL>(n.pos), dpp<CTRL>(n.phys), dpp<CTRL>(n.s) };
-    if (o.pos < n.pos) n = o;
+// Combining the per-wave results that sit in LDS arrays of nw <= 16 entries: lane w takes
+// entry w, one DPP row reduction, lane 0 broadcasts.  Every wave does this for itself
+// (a few dozen instructions) instead of every thread scanning the arrays serially.
+__device__ __forceinline__ double combine_max(const double* arr, int nw, int lane) {
+    double x = (lane < nw) ? arr[lane] : -INFINITY;
+    x = fmax(x, dpp<0xB1>(x)); x = fmax(x, dpp<0x4E>(x)); x = fmax(x, dpp<0x141>(x)); x = fmax(x, dpp<0x140>(x));
+    return readlane_f64(x, 0);
 }
 
-__device__ __forceinline__ Next wave_next(Next n) {
-    next_step<0xB1>(n); next_step<0x4E>(n); next_step<0x141>(n); next_step<0x140>(n);
-    Next r = { __builtin_amdgcn_readlane(n.pos, 0), __builtin_amdgcn_readlane(n.phys, 0), readlane_f64(n.s, 0) };
-#pragma unroll
-    for (int l = 16; l < 64; l += 16) {
-        const Next o = { __builtin_amdgcn_readlane(n.pos, l), __builtin_amdgcn_readlane(n.phys, l),
-                         readlane_f64(n.s, l) };
-        if (o.pos < r.pos) r = o;
-    }
-    return r;
+__device__ __forceinline__ double combine_sum(const double* arr, int nw, int lane) {
+    double x = (lane < nw) ? arr[lane] : 0.0;
+    x = row_allsum(x);
+    return readlane_f64(x, 0);
+}
+
+__device__ __forceinline__ Best combine_argmin(const double* s, const int* pos, const int* phys, int nw, int lane) {
+    Best b = { (lane < nw) ? s[lane] : INFINITY, (lane < nw) ? pos[lane] : 0x7FFFFFFF, (lane < nw) ? phys[lane] : -1 };
+    best_step<0xB1>(b); best_step<0x4E>(b); best_step<0x141>(b); best_step<0x140>(b);
+    return { readlane_f64(b.s, 0), __builtin_amdgcn_readlane(b.pos, 0), __builtin_amdgcn_readlane(b.phys, 0) };
 }
 
 constexpr int MAXPT = 4;       // entries whose a/pos one thread fetches ahead of the streaming loop
@@ -229,8 +248,21 @@ constexpr int NONE_POS = 0x7FFFFFFF;
 // ------------------------------------------------------------------ the kernel
 // Entries attended in step t: the Lc = min(t, m) cached slots, then the incoming
 // token as entry Lc (its row is read from k_new / v_new).  L = Lc + 1.
-template <class TT, int D, int U>
-__global__ __launch_bounds__(1024)
+//
+// Shape of the kernel (one workgroup per unit):
+//   1. small loads (query, score sums, token indices, links, incoming row) are requested,
+//      then the K rows and the V rows of the first chunk, before anything is waited for.
+//      Every wave issues the same loads in straight-line code: s_waitcnt counts are derived
+//      per control-flow path by the compiler, and a conditional request would make every
+//      later wait conservative;
+//   2. streaming pass: logits in fp64 (to LDS), exp(logit - running max) . V accumulated per
+//      16-lane group with an online softmax, so no wave waits for another while data arrives;
+//   3. barrier; bookkeeping of Algorithm 1 in fp64, thread-per-entry, two more barriers
+//      (softmax denominator, arg-min); these barriers wait for LDS traffic only;
+//   4. barrier; combine the per-wave partials into o_t; write-back of score sums, links, the
+//      merged V row and the incoming token's rows into the victim's slot.
+template <class TT, int D, int U, int MAXT>
+__global__ __launch_bounds__(MAXT)
 void wkv_step_kernel(WkvCache c, const void* __restrict__ q_, const void* __restrict__ k_,
                      const void* __restrict__ v_, void* __restrict__ out_, int t)
 {
@@ -249,15 +281,25 @@ void wkv_step_kernel(WkvCache c, const void* __restrict__ q_, const void* __rest
     const int Lc = (t < m) ? t : m;                        // cached entries
     const int L = Lc + 1;                                  // entries attended
     const bool compress = t >= m;                          // the cache would exceed m
+    const int CH = NG * U;                                 // rows per chunk of the workgroup
+    const int nchunks = (L + CH - 1) / CH;
 
     // ---- LDS carve-up
     extern __shared__ double lds[];
-    double* sl   = lds;                                    // [m+1] fp64 logit of every entry
-    double* al   = sl + m + 1;                             // [m+1] score sums a
-    double* wmax = al + m + 1;                             // [16] per-wave maximum logit
-    S*      part = reinterpret_cast<S*>(wmax + 16);        // [NW][D] per-wave P.V partials
-    S*      plw  = part + NW * D;                          // [16] per-wave sum of weights
-    int*    pl   = reinterpret_cast<int*>(plw + 16);       // [m+1] token index of every entry
+    double*   sl        = lds;                             // [m+1] fp64 logit of every entry
+    double*   scl       = sl + m + 1;                      // [m+1] score of every entry
+    double*   wmax      = scl + m + 1;                     // [16] per-wave maximum logit
+    double*   wsum      = wmax + 16;                       // [16] per-wave sum of exponentials
+    double*   best_s    = wsum + 16;                       // [16] per-wave victim: score,
+    S*        part      = reinterpret_cast<S*>(best_s + 16);   // [NW][D] per-wave P.V partials
+    S*        plw       = part + NW * D;                   // [16] per-wave sum of weights
+    S*        pm        = plw + 16;                        // [16] per-wave running maximum
+    int*      best_pos  = reinterpret_cast<int*>(pm + 16);     // [16] ... token index,
+    int*      best_phys = best_pos + 16;                   // [16] ... slot
+    int*      rank_cnt  = best_phys + 16;                  // [16] (first word) entries older than the victim
+    int*      nl        = rank_cnt + 16;                   // [m+1] right-hand neighbour of every entry
+    uint32_t* vj_raw    = reinterpret_cast<uint32_t*>(nl + m + 1);      // [ROWB/4] the victim's V row
+    uint32_t* vr_raw    = vj_raw + ROWB / 4;               // [ROWB/4] its right neighbour's V row
 
     char*       Kc = reinterpret_cast<char*>(c.K) + (size_t)u * m * ROWB;
     char*       Vc = reinterpret_cast<char*>(c.V) + (size_t)u * m * ROWB;
@@ -266,50 +308,72 @@ void wkv_step_kernel(WkvCache c, const void* __restrict__ q_, const void* __rest
     const char* vu = reinterpret_cast<const char*>(v_) + (size_t)u * ROWB;
     double*  au = c.a + (size_t)u * m;
     int32_t* pu = c.pos + (size_t)u * m;
+    int32_t* nu = c.nxt + (size_t)u * m;
 
-    // ---- everything the bookkeeping needs from memory, requested before the streaming loop
+    WKV_MARK(0);
+    // ---- small loads first; raw (clamped addresses, no selects or conversions yet)
+    uint32_t qw[NW32];
+    load_words<NW32>(qu + sub * LANEB, qw);
     double a_reg[MAXPT];
-    int pos_reg[MAXPT];
+    int pos_reg[MAXPT], nxt_reg[MAXPT];
 #pragma unroll
     for (int k = 0; k < MAXPT; ++k) {
         const int i = tid + k * NT;
-        a_reg[k] = (i < Lc) ? au[i] : 0.0;                 // a = [a, 0]
-        pos_reg[k] = (i < Lc) ? pu[i] : ((i == Lc) ? t : NONE_POS);
+        const int ic = (i < Lc) ? i : 0;                   // slot 0 always exists in memory
+        a_reg[k] = au[ic];
+        pos_reg[k] = pu[ic];
+        nxt_reg[k] = nu[ic];
     }
-    float knew_e[EPW], vnew_e[EPW];                        // the incoming row, for wave 0's write-back
-    if (wid == 0) {
+    uint32_t knew_b[EPW], vnew_b[EPW];                     // the incoming row (raw), used by wave 0's write-back
 #pragma unroll
-        for (int e = 0; e < EPW; ++e) {
-            const int col = lane + 64 * e;
-            knew_e[e] = (col < D) ? load_elem<TT>(ku, col) : 0.f;
-            vnew_e[e] = (col < D) ? load_elem<TT>(vu, col) : 0.f;
-        }
+    for (int e = 0; e < EPW; ++e) {
+        const int col = (lane + 64 * e < D) ? lane + 64 * e : 0;
+        knew_b[e] = load_bits<TT>(ku, col);
+        vnew_b[e] = load_bits<TT>(vu, col);
     }
 
-    // ---- the query, pre-scaled by 1/sqrt(d), in fp64
-    double qd[EPL];
+    // ---- streaming pass.  Chunk ch: entries gid + ch*CH + uu*NG, uu < U, of K and of V.
+    // A wave requests its K rows, then its V rows, of a chunk back to back and only then
+    // waits; returns are in order, so the logits of the chunk are ready when its V rows
+    // arrive, and exp(logit - running max) . V is accumulated per 16-lane group with an
+    // online softmax that needs nothing from the other waves.
+    uint32_t kw[U][NW32], vw[U][NW32];
+    auto request = [&](uint32_t (&dst)[U][NW32], const char* cached, const char* incoming, int ch) {
+        const int base = ch * CH + gid;
+        const int dup = (base < L) ? base : 0;             // where out-of-range groups point (harmless duplicate)
+#pragma unroll
+        for (int uu = 0; uu < U; ++uu) {
+            int i = base + uu * NG;
+            if (i >= L) i = dup;
+            const char* rp = (i == Lc) ? incoming : cached + (size_t)i * ROWB;
+            load_words<NW32>(rp + sub * LANEB, dst[uu]);
+        }
+    };
+
+    request(kw, Kc, ku, 0);
+    request(vw, Vc, vu, 0);
+    WKV_MARK(1);
+
+    double qd[EPL];                                        // the query, pre-scaled by 1/sqrt(d), in fp64
     {
-        uint32_t w[NW32]; float x[EPL];
-        load_words<NW32>(qu + sub * LANEB, w);
-        decode<TT, EPL, NW32>(w, x);
+        float x[EPL];
+        decode<TT, EPL, NW32>(qw, x);
         const double scale = 1.0 / sqrt((double)D);
 #pragma unroll
         for (int e = 0; e < EPL; ++e) qd[e] = (double)x[e] * scale;
     }
 
-    // ---- phase 1: stream K, logits in fp64 to LDS
-    double mx = -INFINITY;
-    for (int base = gid; base < L; base += NG * U) {
-        uint32_t kw[U][NW32];
+    double mx = -INFINITY;                                 // maximum logit seen by this group, fp64
+    S m_run = neg_inf<S>(), l_run = (S)0;                  // online softmax state of this group
+    S acc[EPL];
 #pragma unroll
-        for (int uu = 0; uu < U; ++uu) {
-            int i = base + uu * NG;
-            if (i >= L) i = base;                           // harmless duplicate load
-            const char* kp = (i == Lc) ? ku : Kc + (size_t)i * ROWB;
-            load_words<NW32>(kp + sub * LANEB, kw[uu]);
-        }
+    for (int e = 0; e < EPL; ++e) acc[e] = (S)0;
+    auto chunk = [&](int ch) {
+        const int base = ch * CH + gid;
+        S sv[U];
+        S mnew = m_run;
 #pragma unroll
-        for (int uu = 0; uu < U; ++uu) {
+        for (int uu = 0; uu < U; ++uu) {                    // logits q.K / sqrt(d) in fp64, to LDS
             const int i = base + uu * NG;
             float kx[EPL];
             decode<TT, EPL, NW32>(kw[uu], kx);
@@ -321,158 +385,230 @@ void wkv_step_kernel(WkvCache c, const void* __restrict__ q_, const void* __rest
                 if (sub == 0) sl[i] = dot;
                 mx = fmax(mx, dot);
             }
+            sv[uu] = (i < L) ? (S)dot : neg_inf<S>();
+            mnew = (sv[uu] > mnew) ? sv[uu] : mnew;
         }
-    }
-    // mx is uniform within each 16-lane row: combine the four rows of the wave
-    mx = fmax(fmax(readlane_f64(mx, 0), readlane_f64(mx, 16)), fmax(readlane_f64(mx, 32), readlane_f64(mx, 48)));
-    if (lane == 0) wmax[wid] = mx;
+        const S sc = rescale(m_run, mnew);
+        l_run *= sc;
 #pragma unroll
-    for (int k = 0; k < MAXPT; ++k) {
-        const int i = tid + k * NT;
-        if (i < L) { al[i] = a_reg[k]; pl[i] = pos_reg[k]; }
-    }
-    __syncthreads();     // barrier 1: logits, score sums and token indices are staged
-
-    double Mx = wmax[0];
-    for (int w = 1; w < NW; ++w) Mx = fmax(Mx, wmax[w]);
-
-    // state wave 0 carries across barrier 2
-    int dest = t;        // slot that receives the incoming token (fill phase: the next free one)
-    int ev_pos = -1, ev_rank = -1, j = -1, r = -1;
-    double merged[EPW];
-    bool zero_den = false;
-
-    if (wid != 0) {
-        // ---- phase 2, waves 1..NW-1: stream V, accumulate exp(logit - max) . V
-        const int g2 = gid - 4, NG2 = NG - 4;
-        S l_run = (S)0;
-        S acc[EPL];
+        for (int e = 0; e < EPL; ++e) acc[e] *= sc;
 #pragma unroll
-        for (int e = 0; e < EPL; ++e) acc[e] = (S)0;
-        for (int base = g2; base < L; base += NG2 * U) {
-            uint32_t vw[U][NW32];
+        for (int uu = 0; uu < U; ++uu) {                    // exp(logit - running max) . V
+            const S p = rescale(sv[uu], mnew);
+            float vx[EPL];
+            decode<TT, EPL, NW32>(vw[uu], vx);
+            l_run += p;
 #pragma unroll
-            for (int uu = 0; uu < U; ++uu) {
-                int i = base + uu * NG2;
-                if (i >= L) i = base;
-                const char* vp = (i == Lc) ? vu : Vc + (size_t)i * ROWB;
-                load_words<NW32>(vp + sub * LANEB, vw[uu]);
-            }
-#pragma unroll
-            for (int uu = 0; uu < U; ++uu) {
-                const int i = base + uu * NG2;
-                const S p = (i < L) ? soft_exp((S)(sl[(i < L) ? i : base] - Mx)) : (S)0;
-                float vx[EPL];
-                decode<TT, EPL, NW32>(vw[uu], vx);
-                l_run += p;
-#pragma unroll
-                for (int e = 0; e < EPL; ++e) acc[e] += p * (S)vx[e];
-            }
+            for (int e = 0; e < EPL; ++e) acc[e] += p * (S)vx[e];
         }
+        m_run = mnew;
+    };
+    for (int ch = 0; ch + 1 < nchunks; ++ch) {
+        chunk(ch);
+        request(kw, Kc, ku, ch + 1);
+        request(vw, Vc, vu, ch + 1);
+    }
+    chunk(nchunks - 1);                                    // vw keeps the V rows of the last chunk
+    WKV_MARK(2);
+
+    // per-wave partial of o_t: combine the four 16-lane groups, stage for the final combine
+    {
+        S m_w = m_run, l_w = l_run;
+        S acc_w[EPL];
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) acc_w[e] = acc[e];
 #pragma unroll
         for (int off = 16; off <= 32; off <<= 1) {
-            l_run += __shfl_xor(l_run, off);
+            const S mo = __shfl_xor(m_w, off), lo = __shfl_xor(l_w, off);
+            const S M = (mo > m_w) ? mo : m_w;
+            const S sa = rescale(m_w, M), sb = rescale(mo, M);
+            l_w = l_w * sa + lo * sb;
 #pragma unroll
-            for (int e = 0; e < EPL; ++e) acc[e] += __shfl_xor(acc[e], off);
+            for (int e = 0; e < EPL; ++e) acc_w[e] = acc_w[e] * sa + __shfl_xor(acc_w[e], off) * sb;
+            m_w = M;
         }
         if (lane < ROW_LANES) {
 #pragma unroll
-            for (int e = 0; e < EPL; ++e) part[wid * D + lane * EPL + e] = acc[e];
-            if (lane == 0) plw[wid] = l_run;
+            for (int e = 0; e < EPL; ++e) part[wid * D + lane * EPL + e] = acc_w[e];
+            if (lane == 0) { pm[wid] = m_w; plw[wid] = l_w; }
         }
-    } else {
-        // ---- phase 2, wave 0: the bookkeeping of Algorithm 1, in fp64, from LDS
-        double psum = 0.0;
-        for (int i = lane; i < L; i += 64) psum += exp(sl[i] - Mx);
-        const double denom = wave_sum(psum);
+    }
 
-        Best best = { INFINITY, NONE_POS, -1 };
-        int nonfinite = 0;
-        for (int i = lane; i < L; i += 64) {
-            const double p = exp(sl[i] - Mx) / denom;                // A_t[i]
-            const double ai = al[i] + p;                             // a = [a, 0] + A_t
-            al[i] = ai;
-            if (compress) {
-                const int pi = pl[i];
+    // ---- the bookkeeping of Algorithm 1, in fp64, spread over every thread of the workgroup
+    // (thread tid owns entries tid, tid + NT, ...).  The barriers below wait for LDS traffic only.
+#define WKV_LDS_BARRIER() asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory")
+
+    // mx is uniform within each 16-lane row: combine the four rows of the wave
+    mx = fmax(fmax(readlane_f64(mx, 0), readlane_f64(mx, 16)), fmax(readlane_f64(mx, 32), readlane_f64(mx, 48)));
+    if (lane == 0) wmax[wid] = mx;
+    if (tid == 0) rank_cnt[0] = 0;
+    // token order as a linked list: nl[i] = entry that follows entry i; the newest cached
+    // token is followed by the incoming one (entry Lc)
+#pragma unroll
+    for (int k = 0; k < MAXPT; ++k) {
+        const int i = tid + k * NT;
+        if (i < Lc) nl[i] = (nxt_reg[k] < 0) ? Lc : nxt_reg[k];
+    }
+    WKV_MARK(3);
+    WKV_LDS_BARRIER();   // barrier 1: the logit row is complete
+    WKV_MARK(4);
+    const double Mx = combine_max(wmax, NW, lane);
+
+    // rounds of per-entry work: in round k thread tid owns entry tid + k*NT; a wave whose
+    // 64 entries of a round all lie beyond L skips the arithmetic of that round
+    double e_reg[MAXPT];
+    double psum = 0.0;
+#pragma unroll
+    for (int k = 0; k < MAXPT; ++k) {
+        e_reg[k] = 0.0;
+        if (wid * 64 + k * NT < L) {                        // wave-uniform
+            const int i = tid + k * NT;
+            e_reg[k] = (i < L) ? exp(sl[(i < L) ? i : 0] - Mx) : 0.0;
+            psum += e_reg[k];
+        }
+    }
+    if (wid * 64 < L) psum = wave_sum(psum);
+    if (lane == 0) wsum[wid] = psum;
+    WKV_LDS_BARRIER();   // barrier 2: per-wave sums of the softmax denominator
+    WKV_MARK(8);
+    const double inv_denom = 1.0 / combine_sum(wsum, NW, lane);
+
+    Best best = { INFINITY, NONE_POS, -1 };
+    int nonfinite = 0;
+#pragma unroll
+    for (int k = 0; k < MAXPT; ++k) {
+        const int i = tid + k * NT;
+        if (wid * 64 + k * NT < L) {                        // wave-uniform
+            const double p = e_reg[k] * inv_denom;                   // A_t[i]
+            const double ai = ((i < Lc) ? a_reg[k] : 0.0) + p;       // a = [a, 0] + A_t
+            a_reg[k] = ai;
+            const int pi = (i < Lc) ? pos_reg[k] : ((i == Lc) ? t : NONE_POS);
+            pos_reg[k] = pi;
+            if (compress && i < L) {
                 const double ni = (double)(t - pi + 1);              // n: steps this token has been attended
                 double score = (c.score_mode == 0) ? ai / ni : (c.score_mode == 1) ? ai : p;
                 if (!(score == score) || score == INFINITY) { score = INFINITY; nonfinite = 1; }
+                scl[i] = score;
                 if (pi <= t - c.R && pi >= c.n_sink && better(score, pi, best)) best = { score, pi, i };
             }
+        } else {
+            pos_reg[k] = NONE_POS;
         }
-        if (nonfinite) atomicAdd(&c.status[1], 1);
+    }
+    if (nonfinite) atomicAdd(&c.status[1], 1);
 
-        if (compress) {
-            best = wave_argmin(best);
-            j = best.phys;
-            const int pj = best.pos;
-            Next nx = { NONE_POS, -1, 0.0 };
-            int cnt = 0;
-            for (int i = lane; i < L; i += 64) {
-                const int pi = pl[i];
-                if (pi < pj) ++cnt;
-                else if (pi > pj && pi < nx.pos) nx = { pi, i, 0.0 };
-            }
-            nx = wave_next(nx);
-            cnt = wave_sum(cnt);
-            r = nx.phys;
-            ev_pos = pj; ev_rank = cnt;
-            // A candidate and a right neighbour always exist (n_sink + R <= m, and the
-            // incoming token is newer than any candidate).  Should the cache ever be
-            // inconsistent, touch nothing out of range and flag it.
-            if (j < 0 || r < 0) {
-                if (lane == 0) atomicAdd(&c.status[1], 1);
-                j = r = -1;
-            } else {
-                dest = j;
-            }
-        }
-        // score sums back to memory: every entry but the victim; the incoming token's goes to its slot
-        for (int i = lane; i < Lc; i += 64)
-            if (i != j) au[i] = al[i];
-        if (lane == 0 && (!compress || j >= 0)) { au[dest] = al[Lc]; pu[dest] = t; }
-
-        if (compress && j >= 0 && c.merge_mode == 0) {
-            // V[r] <- (abar_j V[j] + abar_r V[r]) / (abar_j + abar_r)     (Algorithm 1, Section IV)
-            const double sj = best.s;
-            const double sr = al[r] / (double)(t - pl[r] + 1);
-            const double den = sj + sr;
-            zero_den = !(den > 0.0);
+    int dest = t;        // slot that receives the incoming token (fill phase: the next free one)
+    int ev_pos = -1, j = -1, r = -1;
+    double sj = 0.0, sr = 0.0;
+    bool sane = true;
+    if (compress) {      // uniform over the workgroup
+        if (wid * 64 < L) best = wave_argmin(best);
+        if (lane == 0) { best_s[wid] = best.s; best_pos[wid] = best.pos; best_phys[wid] = best.phys; }
+        WKV_LDS_BARRIER();   // barrier 3: per-wave victims, and every entry's score
+        WKV_MARK(9);
+        best = combine_argmin(best_s, best_pos, best_phys, NW, lane);
+        j = best.phys; sj = best.s;
+        const int pj = best.pos;
+        ev_pos = pj;
+        // A candidate always exists (n_sink + R <= m) and is never the newest entry, so it has
+        // a right neighbour.  Should the cache ever be inconsistent, touch nothing and flag it.
+        sane = j >= 0 && j < Lc;
+        if (sane) { r = nl[j]; sane = r >= 0 && r <= Lc && r != j; }
+        if (!sane) { if (tid == 0) atomicAdd(&c.status[1], 1); j = r = -1; }
+        else { dest = j; sr = scl[r]; }
+        // the victim's rank in token order, for the log only: counted on the side, read at the end
+        int cnt = 0;
 #pragma unroll
-            for (int e = 0; e < EPW; ++e) {
-                const int col = lane + 64 * e;
-                if (col < D) {
-                    const double vj = (double)load_elem<TT>(Vc + (size_t)j * ROWB, col);
-                    const double vr = (double)((r == Lc) ? vnew_e[e] : load_elem<TT>(Vc + (size_t)r * ROWB, col));
-                    merged[e] = zero_den ? 0.5 * vj + 0.5 * vr : (sj * vj + sr * vr) / den;
-                }
+        for (int k = 0; k < MAXPT; ++k) cnt += (pos_reg[k] < pj) ? 1 : 0;
+        if (wid * 64 < L) {
+            cnt = wave_sum(cnt);
+            if (lane == 0 && cnt) atomicAdd(&rank_cnt[0], cnt);
+        }
+    }
+    WKV_MARK(10);
+
+    // score sums and token indices back to memory: every entry's owner stores its own,
+    // the victim's owner stores nothing, the incoming token's owner stores into the destination
+    if (sane) {
+#pragma unroll
+        for (int k = 0; k < MAXPT; ++k) {
+            const int i = tid + k * NT;
+            if (i < Lc && i != j) {
+                au[i] = a_reg[k];
+                // token order: the newest cached token is now followed by the incoming one (which
+                // lands in slot dest); the victim's predecessor skips over the victim
+                const int n = nxt_reg[k];
+                int nn = n;
+                if (n < 0) nn = dest;
+                else if (n == j) nn = (r == Lc) ? dest : r;
+                if (nn != n) nu[i] = nn;
+            } else if (i == Lc) {
+                au[dest] = a_reg[k]; pu[dest] = t; nu[dest] = -1;
             }
         }
     }
-    __syncthreads();     // barrier 2: every V row has been read, partials are staged
+    WKV_MARK(11);
 
-    if (tid < D) {       // o_t = A_t^T V_t   (Section III-A)
-        const int col = tid;
+    // ---- the merge needs the V rows of the victim and of its right neighbour.  The rows of
+    // the last chunk are still in registers: their holders leave a copy in LDS.  (A row of an
+    // earlier chunk is fetched again by wave 0 below; with one chunk that never happens.)
+    {
+        const int base = (nchunks - 1) * CH + gid;
+#pragma unroll
+        for (int uu = 0; uu < U; ++uu) {
+            const int i = base + uu * NG;
+            if (i < L && (i == j || i == r)) {
+                uint32_t* dstw = (i == j) ? vj_raw : vr_raw;
+#pragma unroll
+                for (int w = 0; w < NW32; ++w) dstw[sub * NW32 + w] = vw[uu][w];
+            }
+        }
+    }
+    WKV_MARK(5);
+    __syncthreads();     // barrier 4: the two rows are staged (per-wave partials since barrier 1)
+    WKV_MARK(6);
+
+    if (tid >= NT - D) {  // o_t = A_t^T V_t   (Section III-A); the last waves, wave 0 has the write-back
+        const int col = tid - (NT - D);
+        S M = pm[0];
+        for (int w = 1; w < NW; ++w) M = (pm[w] > M) ? pm[w] : M;
         S num = (S)0, den = (S)0;
-        for (int w = 1; w < NW; ++w) { num += part[w * D + col]; den += plw[w]; }
+        for (int w = 0; w < NW; ++w) {
+            const S sc = rescale(pm[w], M);
+            num += part[w * D + col] * sc;
+            den += plw[w] * sc;
+        }
         const S o = num / den;
         if constexpr (TT::BYTES == 4) reinterpret_cast<float*>(out_)[(size_t)u * D + col] = (float)o;
         else store_elem<TT>(out_, (size_t)u * D + col, (float)o);
     }
-    if (wid == 0 && (!compress || j >= 0)) {
+    if (wid == 0 && sane) {
         // ---- write-back of the rows: merged value, then the incoming token into its slot
         const bool merge = compress && c.merge_mode == 0;
+        const double den = sj + sr;
+        const bool zero_den = !(den > 0.0);
 #pragma unroll
         for (int e = 0; e < EPW; ++e) {
             const int col = lane + 64 * e;
             if (col < D) {
-                if (merge && r == Lc) {
-                    store_elem_f64<TT>(Vc + (size_t)dest * ROWB, col, merged[e]);   // folded straight into the new token
+                if (merge) {
+                    // V[r] <- (abar_j V[j] + abar_r V[r]) / (abar_j + abar_r)     (Algorithm 1, Section IV)
+                    const int first_held = (nchunks - 1) * CH;     // entries >= this were staged in LDS
+                    const double vj = (double)((j >= first_held) ? load_elem<TT>(vj_raw, col)
+                                                                 : load_elem<TT>(Vc + (size_t)j * ROWB, col));
+                    const double vr = (double)((r >= first_held) ? load_elem<TT>(vr_raw, col)
+                                                                 : load_elem<TT>(Vc + (size_t)r * ROWB, col));
+                    const double x = zero_den ? 0.5 * vj + 0.5 * vr : (sj * vj + sr * vr) / den;
+                    if (r == Lc) {
+                        store_elem_f64<TT>(Vc + (size_t)dest * ROWB, col, x);   // folded straight into the new token
+                    } else {
+                        store_elem_f64<TT>(Vc + (size_t)r * ROWB, col, x);
+                        store_bits<TT>(Vc + (size_t)dest * ROWB, col, vnew_b[e]);
+                    }
                 } else {
-                    if (merge) store_elem_f64<TT>(Vc + (size_t)r * ROWB, col, merged[e]);
-                    store_elem<TT>(Vc + (size_t)dest * ROWB, col, vnew_e[e]);
+                    store_bits<TT>(Vc + (size_t)dest * ROWB, col, vnew_b[e]);
                 }
-                store_elem<TT>(Kc + (size_t)dest * ROWB, col, knew_e[e]);
+                store_bits<TT>(Kc + (size_t)dest * ROWB, col, knew_b[e]);
             }
         }
         if (lane == 0) {
@@ -490,16 +626,34 @@ void wkv_step_kernel(WkvCache c, const void* __restrict__ q_, const void* __rest
     if (tid == 0) {
         const size_t row = (size_t)(t % c.log_cap) * c.units + u;
         c.log_pos[row] = ev_pos;
-        c.log_slot[row] = ev_rank;
+        c.log_slot[row] = (ev_pos >= 0) ? rank_cnt[0] : -1;
     }
+#undef WKV_LDS_BARRIER
+    WKV_MARK(7);
 }
 
-template <class TT, int D>
+// Rows per 16-lane group requested per streaming chunk, sized so that one chunk of K and
+// one of V (both raw, in registers) fit the register file: 128 VGPRs per thread for a
+// 1024-thread workgroup, 256 for 512 threads or fewer.
+template <class TT, int D, int MAXT> constexpr int unroll() {
+    constexpr int words = D / ROW_LANES * TT::BYTES / 4;     // registers per row per lane
+    if (MAXT > 512) return words <= 2 ? 8 : words == 4 ? 7 : 3;
+    return words <= 4 ? 13 : 6;
+}
+
+template <class TT, int D, int MAXT>
+hipError_t prepare(size_t lds)
+{
+    return hipFuncSetAttribute(reinterpret_cast<const void*>(&wkv_step_kernel<TT, D, unroll<TT, D, MAXT>(), MAXT>),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+}
+
+template <class TT, int D, int MAXT>
 hipError_t launch(const WkvCache& c, int threads, size_t lds, const void* q, const void* k,
                   const void* v, void* out, int t, hipStream_t stream)
 {
-    hipLaunchKernelGGL((wkv_step_kernel<TT, D, 4>), dim3(c.units), dim3(threads), lds, stream,
-                       c, q, k, v, out, t);
+    hipLaunchKernelGGL((wkv_step_kernel<TT, D, unroll<TT, D, MAXT>(), MAXT>), dim3(c.units), dim3(threads), lds,
+                       stream, c, q, k, v, out, t);
     return hipGetLastError();
 }
 
@@ -509,10 +663,22 @@ size_t wkv_step_lds_bytes(int m, int dtype, int head_dim, int threads)
 {
     const size_t s = (dtype == 0) ? 8 : 4;     // sizeof(soft_t)
     const size_t nw = (size_t)threads / 64;
-    return ((size_t)m + 1) * 20 + 16 * 8 + (nw * (size_t)head_dim + 16) * s;
+    const size_t rowb = (size_t)head_dim * ((dtype == 0) ? 4 : 2);
+    return ((size_t)m + 1) * 20 + 48 * 8 + (nw * (size_t)head_dim + 32) * s + 48 * 4 + 2 * rowb;
 }
 
 int wkv_step_max_entries(int threads) { return MAXPT * threads; }
+
+hipError_t wkv_step_prepare(int dtype, int head_dim, size_t lds)
+{
+#define WKV_CASE(DT, TT, DD) if (dtype == DT && head_dim == DD) { \
+        hipError_t e = prepare<TT, DD, 1024>(lds); return e != hipSuccess ? e : prepare<TT, DD, 512>(lds); }
+    WKV_CASE(0, TF32, 64)  WKV_CASE(0, TF32, 128)
+    WKV_CASE(1, TF16, 64)  WKV_CASE(1, TF16, 128)  WKV_CASE(1, TF16, 256)
+    WKV_CASE(2, TBF16, 64) WKV_CASE(2, TBF16, 128) WKV_CASE(2, TBF16, 256)
+#undef WKV_CASE
+    return hipErrorInvalidValue;
+}
 
 hipError_t wkv_launch_step(const WkvCache& c, int dtype, int head_dim, int threads,
                            const void* q, const void* k_new, const void* v_new, void* out,
@@ -521,7 +687,9 @@ hipError_t wkv_launch_step(const WkvCache& c, int dtype, int head_dim, int threa
     const size_t lds = wkv_step_lds_bytes(c.m, dtype, head_dim, threads);
     const int ti = (int)t;
 #define WKV_CASE(DT, TT, DD) \
-    if (dtype == DT && head_dim == DD) return launch<TT, DD>(c, threads, lds, q, k_new, v_new, out, ti, stream);
+    if (dtype == DT && head_dim == DD) return threads > 512 \
+        ? launch<TT, DD, 1024>(c, threads, lds, q, k_new, v_new, out, ti, stream) \
+        : launch<TT, DD, 512>(c, threads, lds, q, k_new, v_new, out, ti, stream);
     WKV_CASE(0, TF32, 64)  WKV_CASE(0, TF32, 128)
     WKV_CASE(1, TF16, 64)  WKV_CASE(1, TF16, 128)  WKV_CASE(1, TF16, 256)
     WKV_CASE(2, TBF16, 64) WKV_CASE(2, TBF16, 128) WKV_CASE(2, TBF16, 256)

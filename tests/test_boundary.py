@@ -65,6 +65,6 @@ def test_size_arithmetic():
     # Llama-2-7B-shaped layer, batch 8, budget 410 (the stacked configuration)
     opt = wkv.make_options(8, 32, 128, 410, 32, wkv.WKV_FP16)
     units, L, row = 256, 411, 256
-    assert wkv.wkv_step_bytes(opt) == units * (L * (2 * row + 20) + 9 * row)
+    assert wkv.wkv_step_bytes(opt) == units * (L * (2 * row + 20) + 7 * row)
     kv = 2 * units * L * row
     assert kv < wkv.wkv_workspace_bytes(opt) < kv * 1.1 + (1 << 22)
