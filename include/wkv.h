@@ -79,8 +79,8 @@ typedef struct wkv_options {
  * Create an empty cache (K_0, V_0 empty: Section III-A; a, n empty: Algorithm 1)
  * for batch*heads units on the current HIP device.  The library allocates and
  * owns the device memory: per unit `budget` rows of K and V in `dtype`, one
- * fp64 score sum, one int32 original position and one int32 merge count per
- * slot, plus the eviction log.  The softmax scale is 1/sqrt(head_dim).
+ * fp64 score sum, one int32 original position and one int32 token-order link
+ * per slot, plus the eviction log.  The softmax scale is 1/sqrt(head_dim).
  * *h is written only on success.
  */
 int wkv_create(wkv_handle** h, int batch, int heads, int head_dim,

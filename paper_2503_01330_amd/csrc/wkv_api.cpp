@@ -83,7 +83,7 @@ Sizes sizes(const wkv_options& o)
     s.i32 = units * cap * sizeof(int32_t);
     s.log = logc * units * sizeof(int32_t);
     s.status = 2 * sizeof(int32_t);
-    s.total = 2 * s.kv + s.a + 3 * s.i32 + 2 * s.log + s.status;
+    s.total = 2 * s.kv + s.a + 2 * s.i32 + 2 * s.log + s.status;
     return s;
 }
 
@@ -164,7 +164,7 @@ int wkv_create_ex(wkv_handle** hp, const wkv_options* opt)
 
     struct { void** p; size_t n; int fill; } bufs[] = {
         { &c.K, s.kv, 0 }, { &c.V, s.kv, 0 }, { (void**)&c.a, s.a, 0 },
-        { (void**)&c.pos, s.i32, 0xFF }, { (void**)&c.nxt, s.i32, 0xFF }, { (void**)&c.nmerged, s.i32, 0 },
+        { (void**)&c.pos, s.i32, 0xFF }, { (void**)&c.nxt, s.i32, 0xFF },
         { (void**)&c.log_pos, s.log, 0xFF },
         { (void**)&c.log_slot, s.log, 0xFF }, { (void**)&c.status, s.status, 0 },
     };
@@ -295,8 +295,22 @@ int wkv_state(wkv_handle* h, int what, void* dst, size_t bytes)
                       [&](size_t o, const char* src) { memcpy((char*)dst + o * 8, src, 8); });
     case WKV_POS:
         return gather(c.pos, 4, [&](size_t o, const char* src) { memcpy((char*)dst + o * 4, src, 4); });
-    case WKV_NMERGED:
-        return gather(c.nmerged, 4, [&](size_t o, const char* src) { memcpy((char*)dst + o * 4, src, 4); });
+    case WKV_NMERGED: {
+        // Raw values folded into a slot.  Merging only ever joins a token with its right
+        // neighbour, so a slot holds the contiguous run of tokens that ends at its own key:
+        // the count is the distance to the previous retained key.  Without merging it is 1.
+        const bool merging = h->opt.merge_mode == WKV_MERGE_CONVEX;
+        for (size_t u = 0; u < units; ++u) {
+            int32_t prev = -1;
+            for (size_t l = 0; l < len; ++l) {
+                const int32_t p = pos[u * cap + order[u * len + l]];
+                const int32_t n = merging ? p - prev : 1;
+                memcpy((char*)dst + (u * len + l) * 4, &n, 4);
+                prev = p;
+            }
+        }
+        return WKV_OK;
+    }
     case WKV_COUNT:     // n = steps attended = tokens - pos (every live slot is attended once per step)
         return gather(c.pos, 4, [&](size_t o, const char* src) {
             int32_t p; memcpy(&p, src, 4);
@@ -312,7 +326,7 @@ int wkv_destroy(wkv_handle* h)
     if (!h) return WKV_OK;
     (void)hipDeviceSynchronize();
     WkvCache& c = h->c;
-    void* bufs[] = { c.K, c.V, c.a, c.pos, c.nxt, c.nmerged, c.log_pos, c.log_slot, c.status };
+    void* bufs[] = { c.K, c.V, c.a, c.pos, c.nxt, c.log_pos, c.log_slot, c.status };
     for (void* b : bufs) if (b) (void)hipFree(b);
     delete h;
     return WKV_OK;

@@ -24,7 +24,6 @@ struct WkvCache {
     double*  a;          // [units][m] accumulated attention weight (Algorithm 1's list a), fp64
     int32_t* pos;        // [units][m] original token index of the slot's key
     int32_t* nxt;        // [units][m] slot of the next token in token order, -1 for the newest
-    int32_t* nmerged;    // [units][m] raw values folded into the slot
     int32_t* log_pos;    // [log_cap][units] evicted token index per step (ring), -1 = none
     int32_t* log_slot;   // [log_cap][units] its rank in token order
     int32_t* status;     // [2] {zero-denominator merges, non-finite scores / inconsistencies}

@@ -12,16 +12,18 @@
 //     for d=128 half precision) fully coalesced, and the 16-lane dot-product
 //     reduction is four DPP steps (quad_perm, quad_perm, row_half_mirror,
 //     row_mirror) with no LDS traffic;
-//   * K and V are each streamed exactly once, in one pass.  The logit of every
-//     entry is kept in fp64 and staged in LDS; exp(logit - running max) . V is
-//     accumulated in fp32 (fp64 for an fp32 cache) with an online softmax per
-//     16-lane group and rescaled when the groups are combined;
+//   * K and V are each streamed exactly once.  The K phase leaves the logit of
+//     every entry, in fp64, in LDS; a wave requests its V rows as soon as it has
+//     used its last K row.  The V phase accumulates exp(logit - max) . V in fp32
+//     (fp64 for an fp32 cache);
 //   * the score bookkeeping of Algorithm 1 (softmax denominator, a += A_t,
-//     abar = a/n, arg-min, right neighbour, merge weights) is fp64 throughout,
-//     computed from the staged logit row after the streaming pass.  That costs
-//     one extra convert per K element on a memory-bound kernel and makes the
-//     eviction decision reproduce an fp64 reference exactly (differences ~1e-15
-//     relative in abar) instead of drifting apart after the first near-tie;
+//     abar = a/n, arg-min, right neighbour, merge weights) is done by wave 0
+//     from the staged logit row while V is in flight, so the dependent chain of
+//     the compression hides behind the second half of the memory traffic;
+//   * the bookkeeping is fp64 throughout.  That costs one extra convert per K
+//     element on a memory-bound kernel and makes the eviction decision reproduce
+//     an fp64 reference exactly (differences ~1e-15 relative in abar) instead of
+//     drifting apart after the first near-tie;
 //   * the path is a GEMV per unit with no reuse across units: no MFMA.
 //
 // Slot order in memory is not token order (see wkv_internal.h): the incoming
@@ -250,17 +252,22 @@ constexpr int NONE_POS = 0x7FFFFFFF;
 // token as entry Lc (its row is read from k_new / v_new).  L = Lc + 1.
 //
 // Shape of the kernel (one workgroup per unit):
-//   1. small loads (query, score sums, token indices, links, incoming row) are requested,
-//      then the K rows and the V rows of the first chunk, before anything is waited for.
-//      Every wave issues the same loads in straight-line code: s_waitcnt counts are derived
-//      per control-flow path by the compiler, and a conditional request would make every
-//      later wait conservative;
-//   2. streaming pass: logits in fp64 (to LDS), exp(logit - running max) . V accumulated per
-//      16-lane group with an online softmax, so no wave waits for another while data arrives;
-//   3. barrier; bookkeeping of Algorithm 1 in fp64, thread-per-entry, two more barriers
-//      (softmax denominator, arg-min); these barriers wait for LDS traffic only;
-//   4. barrier; combine the per-wave partials into o_t; write-back of score sums, links, the
-//      merged V row and the incoming token's rows into the victim's slot.
+//   1. small loads (query, score sums, token indices, links, incoming row), then the K
+//      rows of the first chunk, are requested before anything is waited for.  Every wave
+//      issues the same loads in straight-line code: s_waitcnt counts are derived per
+//      control-flow path by the compiler, and a conditional request would make every later
+//      wait conservative;
+//   2. K phase: logits in fp64, to LDS.  A wave requests its first chunk of V rows as soon
+//      as it has used its last K row, so the memory system is never idle but mostly serves
+//      K before V;
+//   3. barrier 1 (LDS traffic only; the V requests stay in flight).  Then wave 0 does the
+//      bookkeeping of Algorithm 1 in fp64 (softmax denominator, a += A_t, abar = a/n,
+//      arg-min, right neighbour) from LDS while V arrives and the waves accumulate
+//      exp(logit - max) . V;
+//   4. barrier 2: victim and neighbour are known.  The groups that hold their V rows (still
+//      in registers) stage them; every thread writes back the score sum and link of the
+//      entry it owns; barrier 3; o_t, the merged V row and the incoming token's rows are
+//      written.
 template <class TT, int D, int U, int MAXT>
 __global__ __launch_bounds__(MAXT)
 void wkv_step_kernel(WkvCache c, const void* __restrict__ q_, const void* __restrict__ k_,
@@ -271,7 +278,7 @@ void wkv_step_kernel(WkvCache c, const void* __restrict__ q_, const void* __rest
     constexpr int NW32 = EPL * TT::BYTES / 4;    // 32-bit words per lane per row
     constexpr int ROWB = D * TT::BYTES;          // bytes per row
     constexpr int LANEB = EPL * TT::BYTES;       // bytes per lane per row
-    constexpr int EPW  = (D + 63) / 64;          // row elements per lane of the bookkeeping wave
+    constexpr int EPW  = (D + 63) / 64;          // row elements per lane when one wave handles a row
 
     const int tid = threadIdx.x, NT = blockDim.x;
     const int NG = NT >> 4, gid = tid >> 4, sub = tid & 15;
@@ -286,20 +293,20 @@ void wkv_step_kernel(WkvCache c, const void* __restrict__ q_, const void* __rest
 
     // ---- LDS carve-up
     extern __shared__ double lds[];
-    double*   sl        = lds;                             // [m+1] fp64 logit of every entry
-    double*   scl       = sl + m + 1;                      // [m+1] score of every entry
-    double*   wmax      = scl + m + 1;                     // [16] per-wave maximum logit
-    double*   wsum      = wmax + 16;                       // [16] per-wave sum of exponentials
-    double*   best_s    = wsum + 16;                       // [16] per-wave victim: score,
-    S*        part      = reinterpret_cast<S*>(best_s + 16);   // [NW][D] per-wave P.V partials
-    S*        plw       = part + NW * D;                   // [16] per-wave sum of weights
-    S*        pm        = plw + 16;                        // [16] per-wave running maximum
-    int*      best_pos  = reinterpret_cast<int*>(pm + 16);     // [16] ... token index,
-    int*      best_phys = best_pos + 16;                   // [16] ... slot
-    int*      rank_cnt  = best_phys + 16;                  // [16] (first word) entries older than the victim
-    int*      nl        = rank_cnt + 16;                   // [m+1] right-hand neighbour of every entry
-    uint32_t* vj_raw    = reinterpret_cast<uint32_t*>(nl + m + 1);      // [ROWB/4] the victim's V row
-    uint32_t* vr_raw    = vj_raw + ROWB / 4;               // [ROWB/4] its right neighbour's V row
+    double*   sl     = lds;                                // [m+1] fp64 logit of every entry
+    double*   el     = sl + m + 1;                         // [m+1] exp(logit - maximum of the producing wave)
+    double*   al     = el + m + 1;                         // [m+1] score sums a
+    double*   wmax   = al + m + 1;                         // [16] per-wave maximum logit
+    double*   wsum   = wmax + 16;                          // [16] per-wave sum of el
+    double*   fw     = wsum + 16;                          // [16] exp(wmax - max) / softmax denominator
+    double*   bk_d   = fw + 16;                            // [16] bookkeeping result: victim's and neighbour's score
+    S*        part   = reinterpret_cast<S*>(bk_d + 16);    // [NW][D] per-wave P.V partials
+    S*        plw    = part + NW * D;                      // [16] per-wave sum of weights
+    int*      pl     = reinterpret_cast<int*>(plw + 16);   // [m+1] token index of every entry
+    int*      nl     = pl + m + 1;                         // [m+1] entry that follows in token order
+    int*      bk_i   = nl + m + 1;                         // [16] bookkeeping result: victim, neighbour, token, rank
+    uint32_t* vj_raw = reinterpret_cast<uint32_t*>(bk_i + 16);   // [ROWB/4] the victim's V row
+    uint32_t* vr_raw = vj_raw + ROWB / 4;                  // [ROWB/4] its right neighbour's V row
 
     char*       Kc = reinterpret_cast<char*>(c.K) + (size_t)u * m * ROWB;
     char*       Vc = reinterpret_cast<char*>(c.V) + (size_t)u * m * ROWB;
@@ -311,7 +318,8 @@ void wkv_step_kernel(WkvCache c, const void* __restrict__ q_, const void* __rest
     int32_t* nu = c.nxt + (size_t)u * m;
 
     WKV_MARK(0);
-    // ---- small loads first; raw (clamped addresses, no selects or conversions yet)
+    // ---- small loads first; raw (clamped addresses, no selects or conversions yet).
+    // Thread tid owns entries tid, tid + NT, ... for staging and write-back.
     uint32_t qw[NW32];
     load_words<NW32>(qu + sub * LANEB, qw);
     double a_reg[MAXPT];
@@ -332,11 +340,7 @@ void wkv_step_kernel(WkvCache c, const void* __restrict__ q_, const void* __rest
         vnew_b[e] = load_bits<TT>(vu, col);
     }
 
-    // ---- streaming pass.  Chunk ch: entries gid + ch*CH + uu*NG, uu < U, of K and of V.
-    // A wave requests its K rows, then its V rows, of a chunk back to back and only then
-    // waits; returns are in order, so the logits of the chunk are ready when its V rows
-    // arrive, and exp(logit - running max) . V is accumulated per 16-lane group with an
-    // online softmax that needs nothing from the other waves.
+    // ---- row requests.  Chunk ch of a matrix: entries gid + ch*CH + uu*NG, uu < U.
     uint32_t kw[U][NW32], vw[U][NW32];
     auto request = [&](uint32_t (&dst)[U][NW32], const char* cached, const char* incoming, int ch) {
         const int base = ch * CH + gid;
@@ -351,8 +355,6 @@ void wkv_step_kernel(WkvCache c, const void* __restrict__ q_, const void* __rest
     };
 
     request(kw, Kc, ku, 0);
-    request(vw, Vc, vu, 0);
-    WKV_MARK(1);
 
     double qd[EPL];                                        // the query, pre-scaled by 1/sqrt(d), in fp64
     {
@@ -363,17 +365,12 @@ void wkv_step_kernel(WkvCache c, const void* __restrict__ q_, const void* __rest
         for (int e = 0; e < EPL; ++e) qd[e] = (double)x[e] * scale;
     }
 
-    double mx = -INFINITY;                                 // maximum logit seen by this group, fp64
-    S m_run = neg_inf<S>(), l_run = (S)0;                  // online softmax state of this group
-    S acc[EPL];
-#pragma unroll
-    for (int e = 0; e < EPL; ++e) acc[e] = (S)0;
-    auto chunk = [&](int ch) {
+    // ---- K phase: logits q.K / sqrt(d) in fp64, to LDS
+    double mx = -INFINITY;
+    auto logits = [&](int ch) {
         const int base = ch * CH + gid;
-        S sv[U];
-        S mnew = m_run;
 #pragma unroll
-        for (int uu = 0; uu < U; ++uu) {                    // logits q.K / sqrt(d) in fp64, to LDS
+        for (int uu = 0; uu < U; ++uu) {
             const int i = base + uu * NG;
             float kx[EPL];
             decode<TT, EPL, NW32>(kw[uu], kx);
@@ -385,206 +382,196 @@ void wkv_step_kernel(WkvCache c, const void* __restrict__ q_, const void* __rest
                 if (sub == 0) sl[i] = dot;
                 mx = fmax(mx, dot);
             }
-            sv[uu] = (i < L) ? (S)dot : neg_inf<S>();
-            mnew = (sv[uu] > mnew) ? sv[uu] : mnew;
         }
-        const S sc = rescale(m_run, mnew);
-        l_run *= sc;
+    };
+    for (int ch = 0; ch + 1 < nchunks; ++ch) { logits(ch); request(kw, Kc, ku, ch + 1); }
+    logits(nchunks - 1);
+    request(vw, Vc, vu, 0);                                // this wave's K is done: its V rows may queue now
+    WKV_MARK(1);
+
+    // mx is uniform within each 16-lane row: combine the four rows of the wave
+    mx = fmax(fmax(readlane_f64(mx, 0), readlane_f64(mx, 16)), fmax(readlane_f64(mx, 32), readlane_f64(mx, 48)));
+    // exp(logit - wave maximum) of the entries this wave produced, one entry per lane: the
+    // fp64 exponentials of the softmax are spread over all waves, ahead of the barrier
+    {
+        double psum = 0.0;
+        const int per_group = (L + NG - 1) / NG;
+        for (int idx = lane; idx < 4 * per_group; idx += 64) {
+            const int i = (4 * wid + (idx & 3)) + NG * (idx >> 2);
+            if (i < L) { const double e = exp(sl[i] - mx); el[i] = e; psum += e; }
+        }
+        psum = wave_sum(psum);
+        if (lane == 0) { wmax[wid] = mx; wsum[wid] = psum; }
+    }
+    // stage what the bookkeeping needs: score sums, token indices, and token order as a linked
+    // list (nl[i] = entry that follows entry i; the newest cached token is followed by the
+    // incoming one, entry Lc)
 #pragma unroll
-        for (int e = 0; e < EPL; ++e) acc[e] *= sc;
+    for (int k = 0; k < MAXPT; ++k) {
+        const int i = tid + k * NT;
+        if (i < Lc) { al[i] = a_reg[k]; pl[i] = pos_reg[k]; nl[i] = (nxt_reg[k] < 0) ? Lc : nxt_reg[k]; }
+        else if (i == Lc) { al[i] = 0.0; pl[i] = t; nl[i] = -1; }      // a = [a, 0]
+    }
+    if (tid == 0) { bk_i[0] = -1; bk_i[1] = -1; bk_i[2] = -1; bk_i[3] = 0; bk_i[4] = 0; }
+    WKV_MARK(2);
+    // barrier 1: logits, exponentials, score sums, token indices and links are staged.  Only
+    // LDS traffic has to be complete; the V rows requested above stay in flight.
+#define WKV_LDS_BARRIER() asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory")
+    WKV_LDS_BARRIER();
+    WKV_MARK(3);
+    const double Mx = combine_max(wmax, NW, lane);
+
+    if (wid == 0) {
+        // ---- wave 0: the bookkeeping of Algorithm 1, in fp64, from LDS, while V arrives
+        {   // softmax denominator from the per-wave partial sums; fw[w] rescales wave w's exponentials
+            const double f = (lane < NW) ? exp(wmax[lane] - Mx) : 0.0;
+            double den = (lane < NW) ? wsum[lane] * f : 0.0;
+            den = readlane_f64(row_allsum(den), 0);
+            if (lane < NW) fw[lane] = f / den;
+        }
+        Best best = { INFINITY, NONE_POS, -1 };
+        int nonfinite = 0;
+        for (int i = lane; i < L; i += 64) {
+            const double p = el[i] * fw[(i & (NG - 1)) >> 2];        // A_t[i]
+            const double ai = al[i] + p;                             // a = [a, 0] + A_t
+            al[i] = ai;
+            if (compress) {
+                const int pi = pl[i];
+                const double ni = (double)(t - pi + 1);              // n: steps this token has been attended
+                double score = (c.score_mode == 0) ? ai / ni : (c.score_mode == 1) ? ai : p;
+                if (!(score == score) || score == INFINITY) { score = INFINITY; nonfinite = 1; }
+                if (pi <= t - c.R && pi >= c.n_sink && better(score, pi, best)) best = { score, pi, i };
+            }
+        }
+        if (nonfinite) atomicAdd(&c.status[1], 1);
+        if (compress) {
+            best = wave_argmin(best);
+            int j = best.phys, r = -1;
+            // A candidate always exists (n_sink + R <= m) and is never the newest entry, so it has
+            // a right neighbour.  Should the cache ever be inconsistent, touch nothing and flag it.
+            bool sane = j >= 0 && j < Lc;
+            if (sane) { r = nl[j]; sane = r >= 0 && r <= Lc && r != j; }
+            if (lane == 0) {
+                if (sane) {
+                    bk_i[0] = j; bk_i[1] = r; bk_i[2] = best.pos;
+                    bk_d[0] = best.s;
+                    bk_d[1] = al[r] / (double)(t - pl[r] + 1);       // abar of the right neighbour
+                } else {
+                    bk_i[3] = 1;
+                    atomicAdd(&c.status[1], 1);
+                }
+            }
+        }
+        WKV_MARK(8);
+    }
+
+    // ---- V phase (all waves): accumulate exp(logit - max) . V
+    S l_run = (S)0;
+    S acc[EPL];
 #pragma unroll
-        for (int uu = 0; uu < U; ++uu) {                    // exp(logit - running max) . V
-            const S p = rescale(sv[uu], mnew);
+    for (int e = 0; e < EPL; ++e) acc[e] = (S)0;
+    auto weighted_sum = [&](int ch) {
+        const int base = ch * CH + gid;
+#pragma unroll
+        for (int uu = 0; uu < U; ++uu) {
+            const int i = base + uu * NG;
+            const S p = (i < L) ? soft_exp((S)(sl[(i < L) ? i : 0] - Mx)) : (S)0;
             float vx[EPL];
             decode<TT, EPL, NW32>(vw[uu], vx);
             l_run += p;
 #pragma unroll
             for (int e = 0; e < EPL; ++e) acc[e] += p * (S)vx[e];
         }
-        m_run = mnew;
     };
-    for (int ch = 0; ch + 1 < nchunks; ++ch) {
-        chunk(ch);
-        request(kw, Kc, ku, ch + 1);
-        request(vw, Vc, vu, ch + 1);
-    }
-    chunk(nchunks - 1);                                    // vw keeps the V rows of the last chunk
-    WKV_MARK(2);
-
-    // per-wave partial of o_t: combine the four 16-lane groups, stage for the final combine
+    weighted_sum(0);                                       // the chunk requested during the K phase
+    for (int ch = 1; ch < nchunks; ++ch) { request(vw, Vc, vu, ch); weighted_sum(ch); }
     {
-        S m_w = m_run, l_w = l_run;
+        S l_w = l_run;
         S acc_w[EPL];
 #pragma unroll
         for (int e = 0; e < EPL; ++e) acc_w[e] = acc[e];
 #pragma unroll
         for (int off = 16; off <= 32; off <<= 1) {
-            const S mo = __shfl_xor(m_w, off), lo = __shfl_xor(l_w, off);
-            const S M = (mo > m_w) ? mo : m_w;
-            const S sa = rescale(m_w, M), sb = rescale(mo, M);
-            l_w = l_w * sa + lo * sb;
+            l_w += __shfl_xor(l_w, off);
 #pragma unroll
-            for (int e = 0; e < EPL; ++e) acc_w[e] = acc_w[e] * sa + __shfl_xor(acc_w[e], off) * sb;
-            m_w = M;
+            for (int e = 0; e < EPL; ++e) acc_w[e] += __shfl_xor(acc_w[e], off);
         }
         if (lane < ROW_LANES) {
 #pragma unroll
             for (int e = 0; e < EPL; ++e) part[wid * D + lane * EPL + e] = acc_w[e];
-            if (lane == 0) { pm[wid] = m_w; plw[wid] = l_w; }
+            if (lane == 0) plw[wid] = l_w;
         }
     }
-
-    // ---- the bookkeeping of Algorithm 1, in fp64, spread over every thread of the workgroup
-    // (thread tid owns entries tid, tid + NT, ...).  The barriers below wait for LDS traffic only.
-#define WKV_LDS_BARRIER() asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory")
-
-    // mx is uniform within each 16-lane row: combine the four rows of the wave
-    mx = fmax(fmax(readlane_f64(mx, 0), readlane_f64(mx, 16)), fmax(readlane_f64(mx, 32), readlane_f64(mx, 48)));
-    if (lane == 0) wmax[wid] = mx;
-    if (tid == 0) rank_cnt[0] = 0;
-    // token order as a linked list: nl[i] = entry that follows entry i; the newest cached
-    // token is followed by the incoming one (entry Lc)
-#pragma unroll
-    for (int k = 0; k < MAXPT; ++k) {
-        const int i = tid + k * NT;
-        if (i < Lc) nl[i] = (nxt_reg[k] < 0) ? Lc : nxt_reg[k];
-    }
-    WKV_MARK(3);
-    WKV_LDS_BARRIER();   // barrier 1: the logit row is complete
     WKV_MARK(4);
-    const double Mx = combine_max(wmax, NW, lane);
-
-    // rounds of per-entry work: in round k thread tid owns entry tid + k*NT; a wave whose
-    // 64 entries of a round all lie beyond L skips the arithmetic of that round
-    double e_reg[MAXPT];
-    double psum = 0.0;
-#pragma unroll
-    for (int k = 0; k < MAXPT; ++k) {
-        e_reg[k] = 0.0;
-        if (wid * 64 + k * NT < L) {                        // wave-uniform
-            const int i = tid + k * NT;
-            e_reg[k] = (i < L) ? exp(sl[(i < L) ? i : 0] - Mx) : 0.0;
-            psum += e_reg[k];
-        }
-    }
-    if (wid * 64 < L) psum = wave_sum(psum);
-    if (lane == 0) wsum[wid] = psum;
-    WKV_LDS_BARRIER();   // barrier 2: per-wave sums of the softmax denominator
-    WKV_MARK(8);
-    const double inv_denom = 1.0 / combine_sum(wsum, NW, lane);
-
-    Best best = { INFINITY, NONE_POS, -1 };
-    int nonfinite = 0;
-#pragma unroll
-    for (int k = 0; k < MAXPT; ++k) {
-        const int i = tid + k * NT;
-        if (wid * 64 + k * NT < L) {                        // wave-uniform
-            const double p = e_reg[k] * inv_denom;                   // A_t[i]
-            const double ai = ((i < Lc) ? a_reg[k] : 0.0) + p;       // a = [a, 0] + A_t
-            a_reg[k] = ai;
-            const int pi = (i < Lc) ? pos_reg[k] : ((i == Lc) ? t : NONE_POS);
-            pos_reg[k] = pi;
-            if (compress && i < L) {
-                const double ni = (double)(t - pi + 1);              // n: steps this token has been attended
-                double score = (c.score_mode == 0) ? ai / ni : (c.score_mode == 1) ? ai : p;
-                if (!(score == score) || score == INFINITY) { score = INFINITY; nonfinite = 1; }
-                scl[i] = score;
-                if (pi <= t - c.R && pi >= c.n_sink && better(score, pi, best)) best = { score, pi, i };
-            }
-        } else {
-            pos_reg[k] = NONE_POS;
-        }
-    }
-    if (nonfinite) atomicAdd(&c.status[1], 1);
-
-    int dest = t;        // slot that receives the incoming token (fill phase: the next free one)
-    int ev_pos = -1, j = -1, r = -1;
-    double sj = 0.0, sr = 0.0;
-    bool sane = true;
-    if (compress) {      // uniform over the workgroup
-        if (wid * 64 < L) best = wave_argmin(best);
-        if (lane == 0) { best_s[wid] = best.s; best_pos[wid] = best.pos; best_phys[wid] = best.phys; }
-        WKV_LDS_BARRIER();   // barrier 3: per-wave victims, and every entry's score
-        WKV_MARK(9);
-        best = combine_argmin(best_s, best_pos, best_phys, NW, lane);
-        j = best.phys; sj = best.s;
-        const int pj = best.pos;
-        ev_pos = pj;
-        // A candidate always exists (n_sink + R <= m) and is never the newest entry, so it has
-        // a right neighbour.  Should the cache ever be inconsistent, touch nothing and flag it.
-        sane = j >= 0 && j < Lc;
-        if (sane) { r = nl[j]; sane = r >= 0 && r <= Lc && r != j; }
-        if (!sane) { if (tid == 0) atomicAdd(&c.status[1], 1); j = r = -1; }
-        else { dest = j; sr = scl[r]; }
-        // the victim's rank in token order, for the log only: counted on the side, read at the end
-        int cnt = 0;
-#pragma unroll
-        for (int k = 0; k < MAXPT; ++k) cnt += (pos_reg[k] < pj) ? 1 : 0;
-        if (wid * 64 < L) {
-            cnt = wave_sum(cnt);
-            if (lane == 0 && cnt) atomicAdd(&rank_cnt[0], cnt);
-        }
-    }
-    WKV_MARK(10);
-
-    // score sums and token indices back to memory: every entry's owner stores its own,
-    // the victim's owner stores nothing, the incoming token's owner stores into the destination
-    if (sane) {
-#pragma unroll
-        for (int k = 0; k < MAXPT; ++k) {
-            const int i = tid + k * NT;
-            if (i < Lc && i != j) {
-                au[i] = a_reg[k];
-                // token order: the newest cached token is now followed by the incoming one (which
-                // lands in slot dest); the victim's predecessor skips over the victim
-                const int n = nxt_reg[k];
-                int nn = n;
-                if (n < 0) nn = dest;
-                else if (n == j) nn = (r == Lc) ? dest : r;
-                if (nn != n) nu[i] = nn;
-            } else if (i == Lc) {
-                au[dest] = a_reg[k]; pu[dest] = t; nu[dest] = -1;
-            }
-        }
-    }
-    WKV_MARK(11);
-
-    // ---- the merge needs the V rows of the victim and of its right neighbour.  The rows of
-    // the last chunk are still in registers: their holders leave a copy in LDS.  (A row of an
-    // earlier chunk is fetched again by wave 0 below; with one chunk that never happens.)
-    {
-        const int base = (nchunks - 1) * CH + gid;
-#pragma unroll
-        for (int uu = 0; uu < U; ++uu) {
-            const int i = base + uu * NG;
-            if (i < L && (i == j || i == r)) {
-                uint32_t* dstw = (i == j) ? vj_raw : vr_raw;
-#pragma unroll
-                for (int w = 0; w < NW32; ++w) dstw[sub * NW32 + w] = vw[uu][w];
-            }
-        }
-    }
+    WKV_LDS_BARRIER();   // barrier 2: victim and neighbour are known, per-wave partials are staged
     WKV_MARK(5);
-    __syncthreads();     // barrier 4: the two rows are staged (per-wave partials since barrier 1)
-    WKV_MARK(6);
 
-    if (tid >= NT - D) {  // o_t = A_t^T V_t   (Section III-A); the last waves, wave 0 has the write-back
+    const int j = bk_i[0], r = bk_i[1], pj = bk_i[2];
+    const bool sane = bk_i[3] == 0;
+    const int dest = compress ? j : t;   // slot that receives the incoming token (fill phase: the next free one)
+
+    if (tid >= NT - D) {  // o_t = A_t^T V_t   (Section III-A); the last waves, wave 0 has the row write-back
         const int col = tid - (NT - D);
-        S M = pm[0];
-        for (int w = 1; w < NW; ++w) M = (pm[w] > M) ? pm[w] : M;
         S num = (S)0, den = (S)0;
-        for (int w = 0; w < NW; ++w) {
-            const S sc = rescale(pm[w], M);
-            num += part[w * D + col] * sc;
-            den += plw[w] * sc;
-        }
+        for (int w = 0; w < NW; ++w) { num += part[w * D + col]; den += plw[w]; }
         const S o = num / den;
         if constexpr (TT::BYTES == 4) reinterpret_cast<float*>(out_)[(size_t)u * D + col] = (float)o;
         else store_elem<TT>(out_, (size_t)u * D + col, (float)o);
     }
+
+    if (sane) {
+        // the merge needs the V rows of the victim and of its right neighbour.  The rows of the
+        // last chunk are still in registers: their holders leave a copy in LDS.  (A row of an
+        // earlier chunk is fetched again by wave 0 below; with one chunk that never happens.)
+        if (compress && c.merge_mode == 0) {
+            const int base = (nchunks - 1) * CH + gid;
+#pragma unroll
+            for (int uu = 0; uu < U; ++uu) {
+                const int i = base + uu * NG;
+                if (i < L && (i == j || i == r)) {
+                    uint32_t* dstw = (i == j) ? vj_raw : vr_raw;
+#pragma unroll
+                    for (int w = 0; w < NW32; ++w) dstw[sub * NW32 + w] = vw[uu][w];
+                }
+            }
+        }
+        // score sums, token indices and links back to memory: every entry's owner stores its
+        // own, the victim's owner stores nothing, the incoming token's owner stores into the
+        // destination.  Links: the newest cached token is now followed by the incoming one
+        // (which lands in slot dest); the victim's predecessor skips over the victim.
+        int cnt = 0;
+#pragma unroll
+        for (int k = 0; k < MAXPT; ++k) {
+            if (k * NT < L) {                               // uniform: skip rounds no thread needs
+                const int i = tid + k * NT;
+                if (i < Lc) {
+                    cnt += (pos_reg[k] < pj) ? 1 : 0;       // the victim's rank in token order, for the log
+                    if (i != j) {
+                        au[i] = al[i];
+                        const int n = nxt_reg[k];
+                        int nn = n;
+                        if (n < 0) nn = dest;
+                        else if (n == j) nn = (r == Lc) ? dest : r;
+                        if (nn != n) nu[i] = nn;
+                    }
+                } else if (i == Lc) {
+                    au[dest] = al[Lc]; pu[dest] = t; nu[dest] = -1;
+                }
+            }
+        }
+        if (compress) {
+            cnt = wave_sum(cnt);
+            if (lane == 0 && cnt) atomicAdd(&bk_i[4], cnt);
+        }
+    }
+    WKV_MARK(6);
+    WKV_LDS_BARRIER();   // barrier 3: the two rows and the rank are staged (global stores keep flying)
+#undef WKV_LDS_BARRIER
+
     if (wid == 0 && sane) {
         // ---- write-back of the rows: merged value, then the incoming token into its slot
         const bool merge = compress && c.merge_mode == 0;
+        const double sj = bk_d[0], sr = bk_d[1];
         const double den = sj + sr;
         const bool zero_den = !(den > 0.0);
 #pragma unroll
@@ -611,24 +598,13 @@ void wkv_step_kernel(WkvCache c, const void* __restrict__ q_, const void* __rest
                 store_bits<TT>(Kc + (size_t)dest * ROWB, col, knew_b[e]);
             }
         }
-        if (lane == 0) {
-            int32_t* nm = c.nmerged + (size_t)u * m;
-            if (merge) {
-                const int nj = nm[j];
-                if (r == Lc) nm[dest] = 1 + nj;
-                else { nm[r] += nj; nm[dest] = 1; }
-                if (zero_den) atomicAdd(&c.status[0], 1);
-            } else {
-                nm[dest] = 1;
-            }
-        }
+        if (lane == 0 && merge && zero_den) atomicAdd(&c.status[0], 1);
     }
     if (tid == 0) {
         const size_t row = (size_t)(t % c.log_cap) * c.units + u;
-        c.log_pos[row] = ev_pos;
-        c.log_slot[row] = (ev_pos >= 0) ? rank_cnt[0] : -1;
+        c.log_pos[row] = (compress && sane) ? pj : -1;
+        c.log_slot[row] = (compress && sane) ? bk_i[4] : -1;
     }
-#undef WKV_LDS_BARRIER
     WKV_MARK(7);
 }
 
@@ -637,8 +613,8 @@ void wkv_step_kernel(WkvCache c, const void* __restrict__ q_, const void* __rest
 // 1024-thread workgroup, 256 for 512 threads or fewer.
 template <class TT, int D, int MAXT> constexpr int unroll() {
     constexpr int words = D / ROW_LANES * TT::BYTES / 4;     // registers per row per lane
-    if (MAXT > 512) return words <= 2 ? 8 : words == 4 ? 7 : 3;
-    return words <= 4 ? 13 : 6;
+    if (MAXT > 512) return words <= 2 ? 8 : words == 4 ? 4 : 2;
+    return words <= 4 ? 8 : 4;
 }
 
 template <class TT, int D, int MAXT>
@@ -664,7 +640,7 @@ size_t wkv_step_lds_bytes(int m, int dtype, int head_dim, int threads)
     const size_t s = (dtype == 0) ? 8 : 4;     // sizeof(soft_t)
     const size_t nw = (size_t)threads / 64;
     const size_t rowb = (size_t)head_dim * ((dtype == 0) ? 4 : 2);
-    return ((size_t)m + 1) * 20 + 48 * 8 + (nw * (size_t)head_dim + 32) * s + 48 * 4 + 2 * rowb;
+    return ((size_t)m + 1) * 32 + 64 * 8 + (nw * (size_t)head_dim + 16) * s + 16 * 4 + 2 * rowb;
 }
 
 int wkv_step_max_entries(int threads) { return MAXPT * threads; }
