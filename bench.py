@@ -28,12 +28,44 @@ def parse():
     ap.add_argument("--layers", type=int, default=0, help="override the number of stacked layers")
     ap.add_argument("--threads", type=int, default=0, help="workgroup size override (256/512/1024)")
     ap.add_argument("--skip-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-seconds", type=float, default=12.0, help="target CPU time of the oracle leg")
+    ap.add_argument("--cpu-core-seconds", type=float, default=20.0,
+                    help="target CPU work (seconds x threads) of the oracle leg")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="run only a plain device copy of known size (for scaling rocprofv3 byte counters)")
     return ap.parse_args()
+
+
+def calibrate_copy():
+    """A plain copy kernel of known size: 64 launches, each reading and writing 1 GiB.
+    Under `rocprofv3 --pmc FETCH_SIZE` (or WRITE_SIZE) the counter value per dispatch divided
+    by 1 GiB is the factor by which the counter has to be scaled on this machine."""
+    import torch
+    n = 1 << 30
+    src = torch.full((n,), 3, dtype=torch.uint8, device="cuda:0")
+    dst = torch.empty_like(src)
+    torch.cuda.synchronize()
+    for _ in range(64):
+        dst.copy_(src)
+    torch.cuda.synchronize()
+    print(json.dumps({"calibration": "device copy", "bytes_read_per_launch": n, "bytes_written_per_launch": n,
+                      "launches": 64}))
+
+
+def measured_traffic(workload):
+    """HBM bytes per launch measured with rocprofv3 counters, if a summary has been committed."""
+    path = os.path.join(ROOT, "profiles", f"traffic_{workload}.json")
+    try:
+        with open(path) as f:
+            return json.load(f).get("hbm_bytes_per_launch")
+    except (OSError, ValueError):
+        return None
 
 
 def main():
     args = parse()
+    if args.calibrate_copy:
+        calibrate_copy()
+        return
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (units are independent and would shard "
               "with no exchange, but no multi-GPU path exists); run with --gpus 1", file=sys.stderr)
@@ -107,10 +139,10 @@ def main():
                                f"{cfg.head_dim} {cfg.dtype}, budget {cfg.budget}, recent window {cfg.recent}, "
                                f"steady state after a {fill}-token fill",
                    "units_per_launch": cfg.units, "launches_per_step": layers,
-                   "threads_per_workgroup": caches[0].opt.threads or "auto",
+                   "threads_per_workgroup": args.threads or "auto",
                    "input_staging_s": round(gen_s, 1)},
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": measured_traffic(args.workload),
                      "kernel": "wkv_step_kernel", "bytes_per_launch": step_bytes,
                      "avg_launch_us": round(kernel_us, 3)},
     }
@@ -118,24 +150,27 @@ def main():
     if not args.skip_cpu_baseline:
         import oracle
         # bounded sample: layer 0, every unit, steady-state steps after the same fill
-        st = synth.Stream(cfg, 0)
+        cores = oracle.threads()
+        ocfg = synth.scaled(cfg, steps=fill + 4096 + 16)
+        st = synth.Stream(ocfg, 0)
         orc = oracle.Oracle(cfg.units, cfg.head_dim, cfg.budget, cfg.recent, storage=cfg.dtype)
         q, k, v = (synth.storage_to_f32(x, cfg.dtype) for x in st.steps(0, fill))
         orc.run(q, k, v, want_out=False)
-        probe = min(8, W + K)
-        q, k, v = (synth.storage_to_f32(x, cfg.dtype) for x in st.steps(fill, total))
+        probe = 16
+        q, k, v = (synth.storage_to_f32(x, cfg.dtype) for x in st.steps(fill, fill + probe))
         c0 = time.perf_counter()
-        orc.run(q[:probe], k[:probe], v[:probe])
+        orc.run(q, k, v)
         per = (time.perf_counter() - c0) / probe
-        n = int(max(1, min(W + K - probe, args.cpu_seconds / per)))
+        n = int(max(64, min(4096, args.cpu_core_seconds / (per * cores))))
+        q, k, v = (synth.storage_to_f32(x, cfg.dtype) for x in st.steps(fill + probe, fill + probe + n))
         c0 = time.perf_counter()
-        orc.run(q[probe:probe + n], k[probe:probe + n], v[probe:probe + n])
+        orc.run(q, k, v)
         cpu_s = time.perf_counter() - c0
         result["cpu_baseline"] = {
             "value": round(cfg.batch * n / (cpu_s * layers), 2), "unit": "tokens/s",
-            "cores": oracle.threads(), "kind": "oracle",
-            "sample": f"layer 0 of {layers}, all {cfg.units} units, {n} steady-state steps in {cpu_s:.1f} s "
-                      f"after the {fill}-token fill; scaled by 1/{layers} layers to whole-token rate",
+            "cores": cores, "kind": "oracle",
+            "sample": f"layer 0 of {layers}, all {cfg.units} units, {n} steady-state steps in {cpu_s:.2f} s wall on "
+                      f"{cores} threads after the {fill}-token fill; scaled by 1/{layers} layers to whole-token rate",
         }
     for c in caches:
         c.close()
