@@ -28,7 +28,9 @@ def parse():
     ap.add_argument("--layers", type=int, default=0, help="override the number of stacked layers")
     ap.add_argument("--threads", type=int, default=0, help="workgroup size override (256/512/1024)")
     ap.add_argument("--skip-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-core-seconds", type=float, default=20.0,
+    ap.add_argument("--also", default="cfg5", choices=["", "cfg2", "cfg4", "cfg5"],
+                    help="second workload measured in the same run and reported under 'also' ('' = none)")
+    ap.add_argument("--cpu-core-seconds", type=float, default=40.0,
                     help="target CPU work (seconds x threads) of the oracle leg")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run only a plain device copy of known size (for scaling rocprofv3 byte counters)")
@@ -76,76 +78,97 @@ def main():
     from paper_2503_01330_amd import binding as wkv
     from paper_2503_01330_amd import synth
 
-    cfg = synth.CONFIGS[args.workload]
-    layers = args.layers or cfg.layers
-    fill = cfg.budget                       # tokens streamed (untimed) until the cache is full
-    W, K = args.warmup, args.steps
-    total = fill + W + K
-    cfg = synth.scaled(cfg, steps=total, layers=max(layers, cfg.layers))
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
-    code = synth.DTYPE_CODE[cfg.dtype]
-    eb = synth.DTYPE_BYTES[cfg.dtype]
 
-    # ---- stage the whole synthetic stream in HBM, one [total, units, d] tensor triple per layer
-    t0 = time.perf_counter()
-    caches, bufs, ptrs = [], [], []
-    for layer in range(layers):
-        q, k, v = synth.Stream(cfg, layer).steps(0, total)
-        tq, tk, tv = (torch.from_numpy(x).to(dev) for x in (q, k, v))
-        out = torch.empty_like(tq)
-        bufs.append((tq, tk, tv, out))
-        ptrs.append(tuple(x.data_ptr() for x in (tq, tk, tv, out)))
-        caches.append(wkv.Cache(cfg.batch, cfg.heads, cfg.head_dim, cfg.budget, cfg.recent, code,
-                                threads=args.threads))
-    gen_s = time.perf_counter() - t0
-    stride = cfg.units * cfg.head_dim * eb
-    stream = torch.cuda.current_stream().cuda_stream
-    handles = [c.h for c in caches]
-    step = wkv.wkv_step
+    def run_workload(name, layers, W, K, threads):
+        """Stage the stream, fill the cache, warm up, time K steps.  Returns the measurements."""
+        cfg = synth.CONFIGS[name]
+        layers = layers or cfg.layers
+        fill = cfg.budget                       # tokens streamed (untimed) until the cache is full
+        total = fill + W + K
+        cfg = synth.scaled(cfg, steps=total, layers=max(layers, cfg.layers))
+        code = synth.DTYPE_CODE[cfg.dtype]
+        eb = synth.DTYPE_BYTES[cfg.dtype]
+        # the whole synthetic stream resident in HBM, one [total, units, d] tensor triple per layer
+        t0 = time.perf_counter()
+        caches, bufs, ptrs = [], [], []
+        for layer in range(layers):
+            q, k, v = synth.Stream(cfg, layer).steps(0, total)
+            tq, tk, tv = (torch.from_numpy(x).to(dev) for x in (q, k, v))
+            out = torch.empty_like(tq)
+            bufs.append((tq, tk, tv, out))
+            ptrs.append(tuple(x.data_ptr() for x in (tq, tk, tv, out)))
+            caches.append(wkv.Cache(cfg.batch, cfg.heads, cfg.head_dim, cfg.budget, cfg.recent, code,
+                                    threads=threads))
+        gen_s = time.perf_counter() - t0
+        stride = cfg.units * cfg.head_dim * eb
+        stream = torch.cuda.current_stream().cuda_stream
+        handles = [c.h for c in caches]
+        step = wkv.wkv_step
 
-    def run(t_lo, t_hi):
-        for t in range(t_lo, t_hi):
-            off = t * stride
-            for h, (pq, pk, pv, po) in zip(handles, ptrs):
-                step(h, pq + off, pk + off, pv + off, po + off, stream)
+        def run(t_lo, t_hi):
+            for t in range(t_lo, t_hi):
+                off = t * stride
+                for h, (pq, pk, pv, po) in zip(handles, ptrs):
+                    step(h, pq + off, pk + off, pv + off, po + off, stream)
 
-    run(0, fill)                 # fill phase: cache grows to its budget
-    run(fill, fill + W)          # steady-state warmup
-    torch.cuda.synchronize()
-    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    w0 = time.perf_counter()
-    ev0.record()
-    run(fill + W, total)
-    ev1.record()
-    torch.cuda.synchronize()
-    wall = time.perf_counter() - w0
-    ev_ms = ev0.elapsed_time(ev1)
+        run(0, fill)                 # fill phase: cache grows to its budget
+        run(fill, fill + W)          # steady-state warmup
+        torch.cuda.synchronize()
+        ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        w0 = time.perf_counter()
+        ev0.record()
+        run(fill + W, total)
+        ev1.record()
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - w0
+        ev_ms = ev0.elapsed_time(ev1)
+        step_bytes = caches[0].step_bytes()              # algorithmic bytes of one launch
+        for c in caches:
+            c.close()
+        del bufs
+        torch.cuda.empty_cache()
+        kernel_us = ev_ms * 1e3 / (K * layers)            # average launch duration incl. gaps (HIP events)
+        achieved = step_bytes / (kernel_us * 1e-6) / 1e9
+        return dict(cfg=cfg, layers=layers, fill=fill, wall=wall, gen_s=gen_s, step_bytes=step_bytes,
+                    kernel_us=kernel_us, achieved=achieved, tokens_per_s=cfg.batch * K / wall)
 
-    launches = K * layers
-    step_bytes = caches[0].step_bytes()                 # algorithmic bytes of one launch
-    kernel_us = ev_ms * 1e3 / launches                   # average launch duration incl. gaps (HIP events)
-    achieved = step_bytes / (kernel_us * 1e-6) / 1e9
-    tokens_per_s = cfg.batch * K / wall
+    W, K = args.warmup, args.steps
+    m = run_workload(args.workload, args.layers, W, K, args.threads)
+    cfg, layers, fill = m["cfg"], m["layers"], m["fill"]
+
+    def roofline(mm, workload):
+        return {"bound": "hbm", "achieved": round(mm["achieved"], 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": round(mm["achieved"] / HBM_PEAK_GBS, 4), "traffic": measured_traffic(workload),
+                "kernel": "wkv_step_kernel", "bytes_per_launch": mm["step_bytes"],
+                "avg_launch_us": round(mm["kernel_us"], 3)}
+
+    def describe(mm, workload):
+        c = mm["cfg"]
+        return (f"{workload}: {mm['layers']} layer(s) x batch {c.batch} x {c.heads} heads x {c.head_dim} {c.dtype}, "
+                f"budget {c.budget}, recent window {c.recent}, steady state after a {mm['fill']}-token fill")
 
     result = {
         "metric": "compressed-cache decode tokens/s at budget B; achieved HBM GB/s % of peak",
-        "value": round(tokens_per_s, 1), "unit": "tokens/s", "n_gpus": 1, "steps": K, "warmup": W,
-        "ms_per_step": round(wall * 1e3 / K, 4), "higher_is_better": True, "scaling": "weak",
+        "value": round(m["tokens_per_s"], 1), "unit": "tokens/s", "n_gpus": 1, "steps": K, "warmup": W,
+        "ms_per_step": round(m["wall"] * 1e3 / K, 4), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": {"fp16": "f16 in, f32/f64 accumulate", "bf16": "bf16 in, f32/f64 accumulate",
                                        "fp32": "f32 in, f64 accumulate"}[cfg.dtype],
         "data": "synthetic",
-        "config": {"workload": f"{args.workload}: {layers} layer(s) x batch {cfg.batch} x {cfg.heads} heads x "
-                               f"{cfg.head_dim} {cfg.dtype}, budget {cfg.budget}, recent window {cfg.recent}, "
-                               f"steady state after a {fill}-token fill",
+        "config": {"workload": describe(m, args.workload),
                    "units_per_launch": cfg.units, "launches_per_step": layers,
                    "threads_per_workgroup": args.threads or "auto",
-                   "input_staging_s": round(gen_s, 1)},
-        "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": measured_traffic(args.workload),
-                     "kernel": "wkv_step_kernel", "bytes_per_launch": step_bytes,
-                     "avg_launch_us": round(kernel_us, 3)},
+                   "input_staging_s": round(m["gen_s"], 1)},
+        "roofline": roofline(m, args.workload),
     }
+    if args.also and args.also != args.workload:
+        # a second workload in the same run, reported next to the headline (not part of `value`):
+        # the batched sweep launches 10x more bytes per kernel, so fixed launch costs weigh less
+        e = run_workload(args.also, 0, W, K, 0)
+        result["also"] = {"config": {"workload": describe(e, args.also)}, "value": round(e["tokens_per_s"], 1),
+                          "unit": "tokens/s", "ms_per_step": round(e["wall"] * 1e3 / K, 4),
+                          "roofline": roofline(e, args.also)}
 
     if not args.skip_cpu_baseline:
         import oracle
@@ -172,8 +195,6 @@ def main():
             "sample": f"layer 0 of {layers}, all {cfg.units} units, {n} steady-state steps in {cpu_s:.2f} s wall on "
                       f"{cores} threads after the {fill}-token fill; scaled by 1/{layers} layers to whole-token rate",
         }
-    for c in caches:
-        c.close()
     print(json.dumps(result), flush=True)
 
 

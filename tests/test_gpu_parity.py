@@ -122,3 +122,56 @@ def test_cfg5_batched_bf16_sampled_units():
     cfg = synth.CONFIGS["cfg5"]
     sel = np.sort(np.random.default_rng(5).choice(cfg.units, 8, replace=False))
     _run(cfg, units_sel=sel, label="cfg5")
+
+
+def test_maximum_budget_uses_the_large_lds_path():
+    """budget = WKV_MAX_BUDGET: the staged score row needs ~140 KB of LDS per workgroup."""
+    m = wkv.WKV_MAX_BUDGET
+    cfg = synth.StreamConfig("maxbudget", 7500, 1, 2, 128, "fp16", m + 48, m, 1)
+    stats = _run(cfg, label="max budget")
+    assert stats["near_ties"] == 0
+
+
+def test_wide_rows_with_a_large_budget():
+    cfg = synth.StreamConfig("wide", 7501, 1, 2, 256, "bf16", 2100, 2047, 5)
+    _run(cfg, label="d256 m2047")
+
+
+def test_single_unit_and_empty_stream():
+    cfg = synth.StreamConfig("one", 7502, 1, 1, 64, "fp16", 90, 20, 4)
+    _run(cfg)
+    cache = wkv.Cache(1, 1, 64, 20, 4, wkv.WKV_FP16)
+    try:
+        assert cache.tokens == 0 and cache.length == 0
+        assert cache.state(wkv.WKV_K).shape == (1, 0, 64)
+        assert cache.state(wkv.WKV_POS).shape == (1, 0)
+        with pytest.raises(wkv.WkvError) as e:
+            cache.evictions(1)                      # nothing logged yet
+        assert e.value.code == wkv.WKV_ESIZE
+    finally:
+        cache.close()
+
+
+def test_host_side_argument_checks_with_a_live_handle():
+    cache = wkv.Cache(1, 2, 64, 8, 2, wkv.WKV_FP16)
+    try:
+        x = torch.zeros(2 * 64 + 8, dtype=torch.float16, device="cuda")
+        ok = x[:128]
+        with pytest.raises(wkv.WkvError) as e:      # misaligned q (2 bytes off a 16-byte boundary)
+            wkv.wkv_step(cache.h, x[1:129].data_ptr(), ok.data_ptr(), ok.data_ptr(), ok.data_ptr(), 0)
+        assert e.value.code == wkv.WKV_EINVAL
+        with pytest.raises(wkv.WkvError) as e:      # null pointer
+            wkv.wkv_step(cache.h, 0, ok.data_ptr(), ok.data_ptr(), ok.data_ptr(), 0)
+        assert e.value.code == wkv.WKV_EINVAL
+        assert cache.tokens == 0                    # rejected steps leave the cache untouched
+        out = torch.empty_like(ok)
+        cache.step(ok, ok, ok, out)
+        small = np.empty(1, np.int32)
+        with pytest.raises(wkv.WkvError) as e:      # readback buffer too small
+            wkv.wkv_state_raw(cache.h, wkv.WKV_POS, small)
+        assert e.value.code == wkv.WKV_ESIZE
+        with pytest.raises(wkv.WkvError) as e:
+            wkv.wkv_state_raw(cache.h, 99, np.empty(64, np.int32))
+        assert e.value.code == wkv.WKV_EINVAL
+    finally:
+        cache.close()
