@@ -11,6 +11,11 @@ import os
 
 import numpy as np
 
+# PyTorch ships its own copy of the HIP runtime.  The tensors handed to wkv_step live in that
+# runtime's context, so it has to be the one libwkv binds to: load torch first, and the
+# dynamic loader resolves libwkv's libamdhip64 dependency to the copy already in the process.
+import torch  # noqa: F401  (imported for its side effect on library resolution)
+
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libwkv.so")
 
