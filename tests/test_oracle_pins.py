@@ -417,3 +417,24 @@ def test_eviction_baseline_variants():
     p = scipy.special.softmax(k[: m + 1, 0].astype(np.float64) @ q[m, 0].astype(np.float64) / math.sqrt(d))
     tova = oracle.Oracle(1, d, m, R, score_mode=2, merge_mode=1).run(q[: m + 1], k[: m + 1], v[: m + 1])
     assert tova["evict_slot"][m, 0] == int(np.argmin(p[: m + 1 - R]))
+
+
+# --------------------------------------------------------------------------
+# the ideal-merge identity of Section III-B: an independent check of the attention conventions
+# --------------------------------------------------------------------------
+@pytest.mark.parametrize("t,d", [(2, 4), (5, 8), (40, 64)])
+def test_ideal_merge_leaves_the_output_unchanged(t, d):
+    from oracle.ideal import ideal_merge, single_step_merge
+    g = rng(500 + t)
+    q, K, V = g.standard_normal(d), g.standard_normal((t, d)) * 1.5, g.standard_normal((t, d))
+    o_full, _ = oracle.attend(q, K, V)
+    v_tilde = ideal_merge(q, K, V)
+    o_merged, _ = oracle.attend(q, K[1:], np.vstack([v_tilde[None], V[2:]]))
+    assert np.allclose(o_merged, o_full, rtol=1e-11, atol=1e-13)
+    # the practical approximation is a convex combination of v_1, v_2 and is *not* exact
+    approx = single_step_merge(q, K, V)
+    lo, hi = np.minimum(V[0], V[1]), np.maximum(V[0], V[1])
+    assert np.all(approx >= lo - 1e-15) and np.all(approx <= hi + 1e-15)
+    if t > 2:
+        o_approx, _ = oracle.attend(q, K[1:], np.vstack([approx[None], V[2:]]))
+        assert not np.allclose(o_approx, o_full, rtol=1e-9, atol=1e-12)
