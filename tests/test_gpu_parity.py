@@ -175,3 +175,38 @@ def test_host_side_argument_checks_with_a_live_handle():
         assert e.value.code == wkv.WKV_EINVAL
     finally:
         cache.close()
+
+
+def test_randomised_shapes():
+    """Many small random configurations (budget, window, sinks, rule variants, head size, dtype,
+    workgroup size, unit count), each streamed past its fill phase and compared in full."""
+    g = np.random.default_rng(20250301)
+    ran = 0
+    for case in range(40):
+        dtype = ["fp16", "bf16", "fp32"][int(g.integers(3))]
+        d = [64, 128, 256][int(g.integers(3))]
+        if dtype == "fp32" and d == 256:
+            d = 128
+        m = int(g.integers(1, 700))
+        R = int(g.integers(1, m + 1)) if g.random() < 0.3 else int(g.integers(1, min(m, 40) + 1))
+        n_sink = int(g.integers(0, min(5, m - R) + 1)) if g.random() < 0.4 else 0
+        mode = int(g.integers(4))       # 0 merge, 1 evict-only, 2 cumulative score, 3 last-step score
+        kw = {}
+        if n_sink:
+            kw["n_sink"] = n_sink
+        if mode >= 1:
+            kw["merge_mode"] = wkv.WKV_MERGE_NONE
+        if mode >= 2:
+            kw["score_mode"] = mode - 1
+        threads = [0, 256, 512, 1024][int(g.integers(4))]
+        if threads and m + 1 > 4 * threads:
+            threads = 0
+        if threads:
+            kw["threads"] = threads
+        batch, heads = int(g.integers(1, 4)), int(g.integers(1, 6))
+        steps = m + int(g.integers(5, 60))
+        cfg = synth.StreamConfig(f"rand{case}", 9000 + case, batch, heads, d, dtype, steps, m, R,
+                                 key_rank=int(g.integers(2, 17)), key_noise=float(g.random() < 0.5) * 0.1)
+        _run(cfg, **kw)
+        ran += 1
+    assert ran == 40
