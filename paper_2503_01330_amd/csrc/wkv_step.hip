@@ -109,7 +109,7 @@ template <class TT> __device__ __forceinline__ float load_elem(const void* base,
     else return __builtin_bit_cast(float, (uint32_t)reinterpret_cast<const uint16_t*>(base)[idx] << 16);
 }
 
-// one storage element as raw bits (no conversion: nothing waits on the load) and back
+// one storage element as raw bits (no conversion: nothing waits on the load)
 template <class TT> __device__ __forceinline__ uint32_t load_bits(const void* base, int idx) {
     if constexpr (TT::BYTES == 4) return reinterpret_cast<const uint32_t*>(base)[idx];
     else return reinterpret_cast<const uint16_t*>(base)[idx];
@@ -118,12 +118,6 @@ template <class TT> __device__ __forceinline__ void store_bits(void* base, int i
     if constexpr (TT::BYTES == 4) reinterpret_cast<uint32_t*>(base)[idx] = b;
     else reinterpret_cast<uint16_t*>(base)[idx] = (uint16_t)b;
 }
-template <class TT> __device__ __forceinline__ float bits_to_f32(uint32_t b) {
-    if constexpr (TT::BYTES == 4) return __builtin_bit_cast(float, b);
-    else if constexpr (__is_same(TT, TF16)) return (float)__builtin_bit_cast(_Float16, (uint16_t)b);
-    else return __builtin_bit_cast(float, b << 16);
-}
-
 __device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
     uint32_t b = __builtin_bit_cast(uint32_t, f);
     if ((b & 0x7FFFFFFFu) > 0x7F800000u) return (uint16_t)((b >> 16) | 0x40);   // NaN stays NaN
@@ -171,13 +165,6 @@ template <class X> __device__ __forceinline__ X row_allsum(X x) {
 
 __device__ __forceinline__ float  soft_exp(float x)  { return __expf(x); }
 __device__ __forceinline__ double soft_exp(double x) { return exp(x); }
-
-template <class S> __device__ __forceinline__ S neg_inf() { return (S)(-INFINITY); }
-
-// scale factor exp(m - M) of a partial whose running maximum is m; 0 for an empty partial
-template <class S> __device__ __forceinline__ S rescale(S m, S M) {
-    return (m == neg_inf<S>()) ? (S)0 : soft_exp(m - M);
-}
 
 // ------------------------------------------------------- wave-level reductions
 // All 64 lanes active.  Results are uniform across the wave and depend only on
@@ -230,18 +217,6 @@ __device__ __forceinline__ double combine_max(const double* arr, int nw, int lan
     double x = (lane < nw) ? arr[lane] : -INFINITY;
     x = fmax(x, dpp<0xB1>(x)); x = fmax(x, dpp<0x4E>(x)); x = fmax(x, dpp<0x141>(x)); x = fmax(x, dpp<0x140>(x));
     return readlane_f64(x, 0);
-}
-
-__device__ __forceinline__ double combine_sum(const double* arr, int nw, int lane) {
-    double x = (lane < nw) ? arr[lane] : 0.0;
-    x = row_allsum(x);
-    return readlane_f64(x, 0);
-}
-
-__device__ __forceinline__ Best combine_argmin(const double* s, const int* pos, const int* phys, int nw, int lane) {
-    Best b = { (lane < nw) ? s[lane] : INFINITY, (lane < nw) ? pos[lane] : 0x7FFFFFFF, (lane < nw) ? phys[lane] : -1 };
-    best_step<0xB1>(b); best_step<0x4E>(b); best_step<0x141>(b); best_step<0x140>(b);
-    return { readlane_f64(b.s, 0), __builtin_amdgcn_readlane(b.pos, 0), __builtin_amdgcn_readlane(b.phys, 0) };
 }
 
 constexpr int MAXPT = 4;       // entries whose a/pos one thread fetches ahead of the streaming loop
