@@ -210,3 +210,34 @@ def test_randomised_shapes():
         _run(cfg, **kw)
         ran += 1
     assert ran == 40
+
+
+def test_two_handles_on_two_streams_do_not_interfere():
+    """Two caches of different shape stepped alternately on two (default-priority) streams give
+    exactly what each gives alone; destroying one leaves the other intact."""
+    cfg_a = synth.StreamConfig("sa", 7600, 1, 4, 128, "fp16", 200, 50, 6)
+    cfg_b = synth.StreamConfig("sb", 7601, 2, 3, 64, "bf16", 200, 33, 4)
+    alone_a = parity.gpu_stream(cfg_a); alone_b = parity.gpu_stream(cfg_b)
+    alone_a["cache"].close(); alone_b["cache"].close()
+
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    runs = []
+    for cfg in (cfg_a, cfg_b):
+        q, k, v = synth.Stream(cfg).steps(0, cfg.steps)
+        tq, tk, tv = (parity.to_device(x, cfg.dtype) for x in (q, k, v))
+        runs.append(dict(cfg=cfg, q=tq, k=tk, v=tv, out=torch.empty_like(tq),
+                         cache=wkv.Cache(cfg.batch, cfg.heads, cfg.head_dim, cfg.budget, cfg.recent,
+                                         synth.DTYPE_CODE[cfg.dtype])))
+    torch.cuda.synchronize()
+    for t in range(200):
+        for r, s in zip(runs, streams):
+            r["cache"].step(r["q"][t], r["k"][t], r["v"][t], r["out"][t], stream=s.cuda_stream)
+    torch.cuda.synchronize()
+    for r, alone in zip(runs, (alone_a, alone_b)):
+        pos, slot = r["cache"].evictions(200)
+        assert np.array_equal(pos, alone["evict_pos"]) and np.array_equal(slot, alone["evict_slot"])
+        assert np.array_equal(parity.out_to_f64(r["out"], r["cfg"].dtype), alone["out"])
+    v_b = runs[1]["cache"].state(wkv.WKV_V).copy()
+    runs[0]["cache"].close()
+    assert np.array_equal(runs[1]["cache"].state(wkv.WKV_V), v_b)
+    runs[1]["cache"].close()
