@@ -130,6 +130,19 @@ int wkv_step(wkv_handle* h, const void* q, const void* k_new, const void* v_new,
  */
 int wkv_state(wkv_handle* h, int what, void* host_dst, size_t bytes);
 
+/*
+ * The inverse of wkv_state: replace the cache by a state given in HOST memory, in token
+ * order, as wkv_state returns it (checkpoint / resume; the method itself has no such step).
+ *   tokens : tokens processed so far (what WKV_STEP returned)
+ *   len    : live slots per unit; must equal min(tokens, budget)
+ *   K, V   : dtype[units,len,d];  score_sum : double[units,len];  pos : int32[units,len],
+ *            strictly increasing within a unit, last entry = tokens-1, all < tokens
+ * Counts and merge counts follow from pos and are not passed.  Synchronous; waits for
+ * enqueued work first.  The eviction log is cleared.  On error the cache is unchanged.
+ */
+int wkv_load(wkv_handle* h, int64_t tokens, int len, const void* K, const void* V,
+             const double* score_sum, const int32_t* pos);
+
 /* Free the cache.  Waits for enqueued work.  NULL is accepted. */
 int wkv_destroy(wkv_handle* h);
 

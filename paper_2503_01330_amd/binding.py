@@ -27,7 +27,7 @@ WKV_MERGE_CONVEX, WKV_MERGE_NONE = 0, 1
 (WKV_STEP, WKV_LEN, WKV_K, WKV_V, WKV_SCORE_SUM, WKV_COUNT, WKV_POS, WKV_NMERGED,
  WKV_EVICT_POS, WKV_EVICT_SLOT, WKV_STATUS) = range(11)
 
-EXPORTS = ("wkv_create", "wkv_create_ex", "wkv_step", "wkv_state", "wkv_destroy",
+EXPORTS = ("wkv_create", "wkv_create_ex", "wkv_step", "wkv_state", "wkv_load", "wkv_destroy",
            "wkv_last_error", "wkv_workspace_bytes", "wkv_step_bytes", "wkv_version")
 
 
@@ -52,6 +52,7 @@ _lib.wkv_create.argtypes = [C.POINTER(C.c_void_p)] + [C.c_int] * 6
 _lib.wkv_create_ex.argtypes = [C.POINTER(C.c_void_p), C.POINTER(wkv_options)]
 _lib.wkv_step.argtypes = [C.c_void_p] * 6
 _lib.wkv_state.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.c_size_t]
+_lib.wkv_load.argtypes = [C.c_void_p, C.c_int64, C.c_int] + [C.c_void_p] * 4
 _lib.wkv_destroy.argtypes = [C.c_void_p]
 _lib.wkv_last_error.restype = C.c_char_p
 _lib.wkv_workspace_bytes.restype = C.c_size_t
@@ -98,6 +99,16 @@ def wkv_step(h, q: int, k_new: int, v_new: int, out: int, stream: int = 0) -> No
 
 def wkv_state_raw(h, what: int, dst: np.ndarray) -> None:
     _check(_lib.wkv_state(h, what, dst.ctypes.data_as(C.c_void_p), dst.nbytes))
+
+
+def wkv_load(h, tokens: int, length: int, K: np.ndarray, V: np.ndarray, score_sum: np.ndarray,
+             pos: np.ndarray) -> None:
+    """Host arrays in token order, as wkv_state returns them."""
+    K, V = np.ascontiguousarray(K), np.ascontiguousarray(V)
+    score_sum = np.ascontiguousarray(score_sum, np.float64)
+    pos = np.ascontiguousarray(pos, np.int32)
+    _check(_lib.wkv_load(h, tokens, length, K.ctypes.data_as(C.c_void_p), V.ctypes.data_as(C.c_void_p),
+                         score_sum.ctypes.data_as(C.c_void_p), pos.ctypes.data_as(C.c_void_p)))
 
 
 def wkv_destroy(h) -> None:
@@ -170,6 +181,9 @@ class Cache:
             wkv_state_raw(self.h, WKV_EVICT_POS, pos)
             wkv_state_raw(self.h, WKV_EVICT_SLOT, slot)
         return pos, slot
+
+    def load(self, tokens, K, V, score_sum, pos):
+        wkv_load(self.h, tokens, pos.shape[1] if pos.ndim == 2 else 0, K, V, score_sum, pos)
 
     def step_bytes(self) -> int:
         return wkv_step_bytes(self.opt)

@@ -95,6 +95,7 @@ struct wkv_handle {
     int device;
     int threads;
     int64_t t;        // tokens processed
+    int64_t log_from; // first step whose eviction log entry is valid (after wkv_load)
 };
 
 extern "C" {
@@ -135,6 +136,7 @@ int wkv_create_ex(wkv_handle** hp, const wkv_options* opt)
     if (h->opt.log_capacity == 0) h->opt.log_capacity = 1024;
     h->threads = threads;
     h->t = 0;
+    h->log_from = 0;
     hipError_t e = hipGetDevice(&h->device);
     if (e != hipSuccess) {
         delete h;
@@ -240,9 +242,9 @@ int wkv_state(wkv_handle* h, int what, void* dst, size_t bytes)
     if (what == WKV_EVICT_POS || what == WKV_EVICT_SLOT) {
         if (bytes % (4 * units) != 0) return fail(WKV_EINVAL, "bytes must be a multiple of 4*units");
         const int64_t n = (int64_t)(bytes / (4 * units));
-        if (n > std::min<int64_t>(T, c.log_cap))
-            return fail(WKV_ESIZE, "asked for %lld steps of log, %lld available", (long long)n,
-                        (long long)std::min<int64_t>(T, c.log_cap));
+        const int64_t avail = std::min<int64_t>(T - h->log_from, c.log_cap);
+        if (n > avail)
+            return fail(WKV_ESIZE, "asked for %lld steps of log, %lld available", (long long)n, (long long)avail);
         const int32_t* src = (what == WKV_EVICT_POS) ? c.log_pos : c.log_slot;
         for (int64_t s = T - n; s < T; ++s) {       // ring: at most two contiguous pieces; keep it simple
             e = hipMemcpy((char*)dst + (size_t)(s - (T - n)) * units * 4, src + (size_t)(s % c.log_cap) * units,
@@ -319,6 +321,50 @@ int wkv_state(wkv_handle* h, int what, void* dst, size_t bytes)
         });
     }
     return fail(WKV_EINVAL, "unknown state item %d", what);
+}
+
+int wkv_load(wkv_handle* h, int64_t tokens, int len, const void* K, const void* V,
+             const double* score_sum, const int32_t* pos)
+{
+    if (!h) return fail(WKV_EINVAL, "null handle");
+    WkvCache& c = h->c;
+    const size_t units = c.units, m = c.m;
+    if (tokens < 0 || tokens >= 0x7FFFFFF0LL) return fail(WKV_EINVAL, "tokens out of range");
+    if (len != (int)std::min<int64_t>(tokens, c.m)) return fail(WKV_EINVAL, "len must equal min(tokens, budget)");
+    if (len > 0 && (!K || !V || !score_sum || !pos)) return fail(WKV_EINVAL, "null state array");
+    for (size_t u = 0; u < units && len > 0; ++u) {
+        const int32_t* pu = pos + u * len;
+        for (int l = 0; l < len; ++l)
+            if (pu[l] < 0 || pu[l] >= tokens || (l > 0 && pu[l] <= pu[l - 1]))
+                return fail(WKV_EINVAL, "pos of unit %zu is not strictly increasing within [0, tokens)", u);
+        if (pu[len - 1] != tokens - 1) return fail(WKV_EINVAL, "the newest token must be retained (unit %zu)", u);
+    }
+    hipError_t e = hipDeviceSynchronize();
+    if (e != hipSuccess) return fail(WKV_EHIP, "hipDeviceSynchronize: %s", hipGetErrorString(e));
+    // device layout: slot l of a unit holds the l-th token in token order, links run l -> l+1
+    const size_t rb = (size_t)h->opt.head_dim * dtype_bytes(h->opt.dtype);
+    std::vector<int32_t> hp(units * m, -1), hn(units * m, -1);
+    std::vector<double> ha(units * m, 0.0);
+    for (size_t u = 0; u < units; ++u)
+        for (int l = 0; l < len; ++l) {
+            hp[u * m + l] = pos[u * len + l];
+            hn[u * m + l] = (l + 1 < len) ? l + 1 : -1;
+            ha[u * m + l] = score_sum[u * len + l];
+        }
+    if (len > 0) {
+        e = hipMemcpy2D(c.K, m * rb, K, (size_t)len * rb, (size_t)len * rb, units, hipMemcpyHostToDevice);
+        if (e == hipSuccess)
+            e = hipMemcpy2D(c.V, m * rb, V, (size_t)len * rb, (size_t)len * rb, units, hipMemcpyHostToDevice);
+    }
+    if (e == hipSuccess) e = hipMemcpy(c.a, ha.data(), ha.size() * sizeof(double), hipMemcpyHostToDevice);
+    if (e == hipSuccess) e = hipMemcpy(c.pos, hp.data(), hp.size() * 4, hipMemcpyHostToDevice);
+    if (e == hipSuccess) e = hipMemcpy(c.nxt, hn.data(), hn.size() * 4, hipMemcpyHostToDevice);
+    if (e == hipSuccess) e = hipMemset(c.log_pos, 0xFF, (size_t)c.log_cap * units * 4);
+    if (e == hipSuccess) e = hipMemset(c.log_slot, 0xFF, (size_t)c.log_cap * units * 4);
+    if (e != hipSuccess) return fail(WKV_EHIP, "uploading the state: %s (the cache may be partly overwritten)", hipGetErrorString(e));
+    h->t = tokens;
+    h->log_from = tokens;
+    return WKV_OK;
 }
 
 int wkv_destroy(wkv_handle* h)

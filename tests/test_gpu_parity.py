@@ -241,3 +241,45 @@ def test_two_handles_on_two_streams_do_not_interfere():
     runs[0]["cache"].close()
     assert np.array_equal(runs[1]["cache"].state(wkv.WKV_V), v_b)
     runs[1]["cache"].close()
+
+
+def test_checkpoint_and_resume():
+    """State read back with wkv_state and loaded into a fresh handle continues with the same
+    evictions and retained keys.  A loaded cache sits in token order in memory, the original does
+    not, so floating-point sums run in another order: values agree to rounding, not bit for bit."""
+    cfg = synth.StreamConfig("ckpt", 7700, 2, 3, 128, "fp16", 400, 60, 7)
+    q, k, v = synth.Stream(cfg).steps(0, cfg.steps)
+    tq, tk, tv = (parity.to_device(x, cfg.dtype) for x in (q, k, v))
+    code = synth.DTYPE_CODE[cfg.dtype]
+    for split in (25, 60, 233):                      # during the fill, at the boundary, in steady state
+        a = wkv.Cache(cfg.batch, cfg.heads, cfg.head_dim, cfg.budget, cfg.recent, code)
+        b = wkv.Cache(cfg.batch, cfg.heads, cfg.head_dim, cfg.budget, cfg.recent, code)
+        out_a, out_b = torch.empty_like(tq), torch.empty_like(tq)
+        try:
+            for t in range(split):
+                a.step(tq[t], tk[t], tv[t], out_a[t])
+            b.load(a.tokens, a.state(wkv.WKV_K), a.state(wkv.WKV_V), a.state(wkv.WKV_SCORE_SUM), a.state(wkv.WKV_POS))
+            assert b.tokens == split and b.length == min(split, cfg.budget)
+            with pytest.raises(wkv.WkvError):
+                b.evictions(1)                        # the log starts afresh after a load
+            for t in range(split, cfg.steps):
+                a.step(tq[t], tk[t], tv[t], out_a[t])
+                b.step(tq[t], tk[t], tv[t], out_b[t])
+            torch.cuda.synchronize()
+            n = cfg.steps - split
+            parity.check_outputs(parity.out_to_f64(out_b[split:], cfg.dtype),
+                                 parity.out_to_f64(out_a[split:], cfg.dtype), cfg.dtype)
+            pa, sa = a.evictions(n); pb, sb = b.evictions(n)
+            assert np.array_equal(pa, pb) and np.array_equal(sa, sb)
+            for what in (wkv.WKV_K, wkv.WKV_POS, wkv.WKV_NMERGED, wkv.WKV_COUNT):
+                assert np.array_equal(a.state(what), b.state(what))
+            assert np.allclose(a.state(wkv.WKV_SCORE_SUM), b.state(wkv.WKV_SCORE_SUM), rtol=1e-12, atol=0)
+            parity.check_outputs(b.state(wkv.WKV_V).astype(np.float64), a.state(wkv.WKV_V).astype(np.float64),
+                                 cfg.dtype, what="values")
+            # malformed states are rejected and leave the handle as it was
+            pos = a.state(wkv.WKV_POS).copy(); pos[0, 0] = pos[0, 1]
+            with pytest.raises(wkv.WkvError) as e:
+                b.load(a.tokens, a.state(wkv.WKV_K), a.state(wkv.WKV_V), a.state(wkv.WKV_SCORE_SUM), pos)
+            assert e.value.code == wkv.WKV_EINVAL and b.tokens == cfg.steps
+        finally:
+            a.close(); b.close()
