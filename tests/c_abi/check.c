@@ -1,0 +1,86 @@
+/*
+ * A plain C caller of libwkv: no Python, no PyTorch.  It streams a few tokens through a
+ * small cache on device 0 and checks facts that hold for any input: with every value row
+ * equal to one constant vector, every output and every (merged) cached value equals that
+ * vector; the cache holds min(tokens, budget) slots; token positions are strictly increasing
+ * and end at the newest token; merge counts sum to the number of tokens; the eviction log
+ * names tokens outside the recent window.  Prints "c_abi ok" and exits 0 on success.
+ */
+#include <hip/hip_runtime_api.h>
+#include <math.h>
+#include <stdio.h>
+#include <stdlib.h>
+
+#include "../../include/wkv.h"
+
+#define B 2
+#define H 3
+#define D 64
+#define M 5
+#define R 2
+#define T 23
+#define UNITS (B * H)
+
+#define HIP(x) do { hipError_t e_ = (x); if (e_ != hipSuccess) { printf("hip: %s (line %d)\n", hipGetErrorString(e_), __LINE__); return 2; } } while (0)
+#define WKV(x) do { int r_ = (x); if (r_ != WKV_OK) { printf("wkv: %d %s (line %d)\n", r_, wkv_last_error(), __LINE__); return 3; } } while (0)
+#define CHECK(c) do { if (!(c)) { printf("check failed: %s (line %d)\n", #c, __LINE__); return 4; } } while (0)
+
+static float lcg(unsigned* s) { *s = *s * 1664525u + 1013904223u; return ((*s >> 8) & 0xFFFF) / 32768.0f - 1.0f; }
+
+int main(void)
+{
+    const size_t n = (size_t)UNITS * D;
+    float *hq = malloc(n * 4), *hk = malloc(n * 4), *hv = malloc(n * 4), *ho = malloc(n * 4);
+    float *dq, *dk, *dv, *dout;
+    HIP(hipMalloc((void**)&dq, n * 4)); HIP(hipMalloc((void**)&dk, n * 4));
+    HIP(hipMalloc((void**)&dv, n * 4)); HIP(hipMalloc((void**)&dout, n * 4));
+    wkv_handle* h = NULL;
+    CHECK(wkv_create(&h, B, H, 96, M, R, WKV_FP32) == WKV_EINVAL && h == NULL);   /* bad head_dim is refused */
+    WKV(wkv_create(&h, B, H, D, M, R, WKV_FP32));
+
+    float cvec[D];
+    unsigned seed = 7;
+    for (int c = 0; c < D; ++c) cvec[c] = lcg(&seed);
+    for (int t = 0; t < T; ++t) {
+        for (size_t i = 0; i < n; ++i) { hq[i] = lcg(&seed); hk[i] = lcg(&seed); hv[i] = cvec[i % D]; }
+        HIP(hipMemcpy(dq, hq, n * 4, hipMemcpyHostToDevice));
+        HIP(hipMemcpy(dk, hk, n * 4, hipMemcpyHostToDevice));
+        HIP(hipMemcpy(dv, hv, n * 4, hipMemcpyHostToDevice));
+        WKV(wkv_step(h, dq, dk, dv, dout, NULL));
+        HIP(hipMemcpy(ho, dout, n * 4, hipMemcpyDeviceToHost));
+        for (size_t i = 0; i < n; ++i) CHECK(fabsf(ho[i] - cvec[i % D]) <= 1e-5f * fabsf(cvec[i % D]) + 1e-7f);
+    }
+
+    int64_t tokens = 0; int32_t len = 0;
+    WKV(wkv_state(h, WKV_STEP, &tokens, sizeof tokens));
+    WKV(wkv_state(h, WKV_LEN, &len, sizeof len));
+    CHECK(tokens == T && len == M);
+    int32_t pos[UNITS * M], nm[UNITS * M], cnt[UNITS * M], ev[T * UNITS];
+    float V[UNITS * M * D];
+    WKV(wkv_state(h, WKV_POS, pos, sizeof pos));
+    WKV(wkv_state(h, WKV_NMERGED, nm, sizeof nm));
+    WKV(wkv_state(h, WKV_COUNT, cnt, sizeof cnt));
+    WKV(wkv_state(h, WKV_V, V, sizeof V));
+    WKV(wkv_state(h, WKV_EVICT_POS, ev, sizeof ev));
+    CHECK(wkv_state(h, WKV_POS, pos, sizeof pos - 4) == WKV_ESIZE);
+    for (int u = 0; u < UNITS; ++u) {
+        int total = 0;
+        for (int l = 0; l < M; ++l) {
+            if (l) CHECK(pos[u * M + l] > pos[u * M + l - 1]);
+            CHECK(cnt[u * M + l] == T - pos[u * M + l]);
+            total += nm[u * M + l];
+            for (int c = 0; c < D; ++c)
+                CHECK(fabsf(V[(u * M + l) * D + c] - cvec[c]) <= 1e-6f * fabsf(cvec[c]) + 1e-7f);
+        }
+        CHECK(pos[u * M + M - 1] == T - 1 && total == T);
+        for (int t = 0; t < T; ++t) {
+            const int e = ev[t * UNITS + u];
+            if (t < M) CHECK(e == -1); else CHECK(e >= 0 && e <= t - R);
+        }
+    }
+    WKV(wkv_destroy(h));
+    HIP(hipFree(dq)); HIP(hipFree(dk)); HIP(hipFree(dv)); HIP(hipFree(dout));
+    free(hq); free(hk); free(hv); free(ho);
+    printf("c_abi ok\n");
+    return 0;
+}

@@ -283,3 +283,13 @@ def test_checkpoint_and_resume():
             assert e.value.code == wkv.WKV_EINVAL and b.tokens == cfg.steps
         finally:
             a.close(); b.close()
+
+
+def test_plain_c_caller():
+    """tests/c_abi/check.c drives libwkv from C (hipMalloc'ed buffers, no Python in the loop)."""
+    import os
+    import subprocess
+    exe = os.path.join(os.path.dirname(os.path.abspath(__file__)), "c_abi", "check")
+    assert os.path.exists(exe), "build it first: python -c 'import __graft_entry__ as g; g.build()'"
+    r = subprocess.run([exe], capture_output=True, text=True, timeout=120)
+    assert r.returncode == 0 and "c_abi ok" in r.stdout, r.stdout + r.stderr
