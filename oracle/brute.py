@@ -5,7 +5,7 @@ One (sequence, head) unit, Python floats (IEEE double), Python lists with
 and meant for tiny inputs.  It exists to pin the C oracle (wkv_oracle.c): the
 two are written separately and must agree exactly on small random streams.
 
-Readings taken where the paper is silent (all listed in the design notes):
+Readings taken where the paper is silent:
   * logits are scaled by 1/sqrt(d) (Section III-B writes the scale, III-A omits it);
   * the attention of step t runs over the cache *including* the new token and
     *before* compression (Algorithm 1 obtains A_t ahead of the capacity test);

@@ -11,6 +11,13 @@
  * algorithm's own steps in the paper's order: ordered arrays, literal removal
  * of index j, explicit count list n.  No blocking, no fusion, no intrinsics.
  *
+ * Pins: every function below is checked in tests/test_oracle_pins.py against something
+ * other than itself (numbers the paper prints, library softmax attention, closed forms,
+ * invariants, a separately written list simulator).  Parity unpinned: only what no
+ * implementation-free fact covers -- how close the compressed cache stays to full
+ * attention (the paper's evidence is perplexity on data that is not available), and the
+ * two eviction-rule variants beyond the special cases tested.
+ *
  * It shares no code with the HIP library and nothing on the product path may
  * link or call it; only tests, the smoke check and the benchmark's
  * cpu_baseline leg use it.

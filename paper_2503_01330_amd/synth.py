@@ -56,7 +56,7 @@ class StreamConfig:
         return self.batch * self.heads
 
 
-# The five configurations of the build's baseline definition.
+# The five synthetic configurations (shapes of a Llama-2-7B-style workload, see the module docstring).
 CONFIGS: Dict[str, StreamConfig] = {
     "cfg1": StreamConfig("cfg1", 1001, 1, 4, 64, "fp32", 512, 64, 16,
                          key_rank=8, key_noise=0.1),
