@@ -114,6 +114,12 @@ template <class TT> __device__ __forceinline__ uint32_t load_bits(const void* ba
     if constexpr (TT::BYTES == 4) return reinterpret_cast<const uint32_t*>(base)[idx];
     else return reinterpret_cast<const uint16_t*>(base)[idx];
 }
+// raw bits of one storage element -> fp32
+template <class TT> __device__ __forceinline__ float bits_elem(uint32_t b) {
+    if constexpr (TT::BYTES == 4) return __builtin_bit_cast(float, b);
+    else if constexpr (__is_same(TT, TF16)) return (float)__builtin_bit_cast(_Float16, (uint16_t)b);
+    else return __builtin_bit_cast(float, b << 16);
+}
 template <class TT> __device__ __forceinline__ void store_bits(void* base, int idx, uint32_t b) {
     if constexpr (TT::BYTES == 4) reinterpret_cast<uint32_t*>(base)[idx] = b;
     else reinterpret_cast<uint16_t*>(base)[idx] = (uint16_t)b;
@@ -243,7 +249,11 @@ constexpr int NONE_POS = 0x7FFFFFFF;
 //      in registers) stage them; every thread writes back the score sum and link of the
 //      entry it owns; barrier 3; o_t, the merged V row and the incoming token's rows are
 //      written.
-template <class TT, int D, int U, int MAXT>
+//
+// SEP: the incoming token is attended outside the chunked streaming (by the wave whose group
+// would have held it).  Chosen by the host when the budget is a multiple of the chunk, where
+// entry m would otherwise cost every wave one more, almost empty, chunk of K and of V.
+template <class TT, int D, int U, int MAXT, bool SEP>
 __global__ __launch_bounds__(MAXT)
 void wkv_step_kernel(WkvCache c, const void* __restrict__ q_, const void* __restrict__ k_,
                      const void* __restrict__ v_, void* __restrict__ out_, int t)
@@ -264,7 +274,10 @@ void wkv_step_kernel(WkvCache c, const void* __restrict__ q_, const void* __rest
     const int L = Lc + 1;                                  // entries attended
     const bool compress = t >= m;                          // the cache would exceed m
     const int CH = NG * U;                                 // rows per chunk of the workgroup
-    const int nchunks = (L + CH - 1) / CH;
+    const int Ls = SEP ? Lc : L;                           // entries streamed in chunks
+    const int nchunks = (Ls > CH) ? (Ls + CH - 1) / CH : 1;
+    const int g_in = Lc & (NG - 1);                        // SEP: the group that owns the incoming entry
+    const bool own_in = SEP && wid == (g_in >> 2);         //      and its wave
 
     // ---- LDS carve-up
     extern __shared__ double lds[];
@@ -314,17 +327,19 @@ void wkv_step_kernel(WkvCache c, const void* __restrict__ q_, const void* __rest
         knew_b[e] = load_bits<TT>(ku, col);
         vnew_b[e] = load_bits<TT>(vu, col);
     }
+    [[maybe_unused]] uint32_t kin[NW32];                    // SEP: the incoming key in row layout
+    if constexpr (SEP) load_words<NW32>(ku + sub * LANEB, kin);
 
     // ---- row requests.  Chunk ch of a matrix: entries gid + ch*CH + uu*NG, uu < U.
     uint32_t kw[U][NW32], vw[U][NW32];
     auto request = [&](uint32_t (&dst)[U][NW32], const char* cached, const char* incoming, int ch) {
         const int base = ch * CH + gid;
-        const int dup = (base < L) ? base : 0;             // where out-of-range groups point (harmless duplicate)
+        const int dup = (base < Ls) ? base : 0;            // where out-of-range groups point (harmless duplicate)
 #pragma unroll
         for (int uu = 0; uu < U; ++uu) {
             int i = base + uu * NG;
-            if (i >= L) i = dup;
-            const char* rp = (i == Lc) ? incoming : cached + (size_t)i * ROWB;
+            if (i >= Ls) i = dup;
+            const char* rp = (!SEP && i == Lc) ? incoming : cached + (size_t)i * ROWB;
             load_words<NW32>(rp + sub * LANEB, dst[uu]);
         }
     };
@@ -353,14 +368,28 @@ void wkv_step_kernel(WkvCache c, const void* __restrict__ q_, const void* __rest
 #pragma unroll
             for (int e = 0; e < EPL; ++e) dot = fma((double)kx[e], qd[e], dot);
             dot = row_allsum(dot);
-            if (i < L) {
+            if (i < Ls) {
                 if (sub == 0) sl[i] = dot;
                 mx = fmax(mx, dot);
             }
         }
     };
+    if constexpr (SEP) {
+        if (own_in) {                                      // the incoming token's logit (its key arrived first)
+            float kx[EPL];
+            decode<TT, EPL, NW32>(kin, kx);
+            double dot = 0.0;
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) dot = fma((double)kx[e], qd[e], dot);
+            dot = row_allsum(dot);
+            if (gid == g_in && sub == 0) sl[Lc] = dot;
+            mx = fmax(mx, dot);
+        }
+    }
     for (int ch = 0; ch + 1 < nchunks; ++ch) { logits(ch); request(kw, Kc, ku, ch + 1); }
     logits(nchunks - 1);
+    [[maybe_unused]] uint32_t vin[NW32];                    // SEP: the incoming value in row layout
+    if constexpr (SEP) load_words<NW32>(vu + sub * LANEB, vin);
     request(vw, Vc, vu, 0);                                // this wave's K is done: its V rows may queue now
     WKV_MARK(1);
 
@@ -450,7 +479,7 @@ void wkv_step_kernel(WkvCache c, const void* __restrict__ q_, const void* __rest
 #pragma unroll
         for (int uu = 0; uu < U; ++uu) {
             const int i = base + uu * NG;
-            const S p = (i < L) ? soft_exp((S)(sl[(i < L) ? i : 0] - Mx)) : (S)0;
+            const S p = (i < Ls) ? soft_exp((S)(sl[(i < Ls) ? i : 0] - Mx)) : (S)0;
             float vx[EPL];
             decode<TT, EPL, NW32>(vw[uu], vx);
             l_run += p;
@@ -458,6 +487,16 @@ void wkv_step_kernel(WkvCache c, const void* __restrict__ q_, const void* __rest
             for (int e = 0; e < EPL; ++e) acc[e] += p * (S)vx[e];
         }
     };
+    if constexpr (SEP) {
+        if (own_in) {                                      // the incoming token, counted by its group only
+            const S p = (gid == g_in) ? soft_exp((S)(sl[Lc] - Mx)) : (S)0;
+            float vx[EPL];
+            decode<TT, EPL, NW32>(vin, vx);
+            l_run += p;
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) acc[e] += p * (S)vx[e];
+        }
+    }
     weighted_sum(0);                                       // the chunk requested during the K phase
     for (int ch = 1; ch < nchunks; ++ch) { request(vw, Vc, vu, ch); weighted_sum(ch); }
     {
@@ -503,7 +542,7 @@ void wkv_step_kernel(WkvCache c, const void* __restrict__ q_, const void* __rest
 #pragma unroll
             for (int uu = 0; uu < U; ++uu) {
                 const int i = base + uu * NG;
-                if (i < L && (i == j || i == r)) {
+                if (i < Ls && (i == j || i == r)) {
                     uint32_t* dstw = (i == j) ? vj_raw : vr_raw;
 #pragma unroll
                     for (int w = 0; w < NW32; ++w) dstw[sub * NW32 + w] = vw[uu][w];
@@ -558,8 +597,9 @@ void wkv_step_kernel(WkvCache c, const void* __restrict__ q_, const void* __rest
                     const int first_held = (nchunks - 1) * CH;     // entries >= this were staged in LDS
                     const double vj = (double)((j >= first_held) ? load_elem<TT>(vj_raw, col)
                                                                  : load_elem<TT>(Vc + (size_t)j * ROWB, col));
-                    const double vr = (double)((r >= first_held) ? load_elem<TT>(vr_raw, col)
-                                                                 : load_elem<TT>(Vc + (size_t)r * ROWB, col));
+                    const double vr = (double)((SEP && r == Lc) ? bits_elem<TT>(vnew_b[e])
+                                               : (r >= first_held) ? load_elem<TT>(vr_raw, col)
+                                                                   : load_elem<TT>(Vc + (size_t)r * ROWB, col));
                     const double x = zero_den ? 0.5 * vj + 0.5 * vr : (sj * vj + sr * vr) / den;
                     if (r == Lc) {
                         store_elem_f64<TT>(Vc + (size_t)dest * ROWB, col, x);   // folded straight into the new token
@@ -595,7 +635,11 @@ template <class TT, int D, int MAXT> constexpr int unroll() {
 template <class TT, int D, int MAXT>
 hipError_t prepare(size_t lds)
 {
-    return hipFuncSetAttribute(reinterpret_cast<const void*>(&wkv_step_kernel<TT, D, unroll<TT, D, MAXT>(), MAXT>),
+    constexpr int U = unroll<TT, D, MAXT>();
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&wkv_step_kernel<TT, D, U, MAXT, false>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    return hipFuncSetAttribute(reinterpret_cast<const void*>(&wkv_step_kernel<TT, D, U, MAXT, true>),
                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
 }
 
@@ -603,8 +647,14 @@ template <class TT, int D, int MAXT>
 hipError_t launch(const WkvCache& c, int threads, size_t lds, const void* q, const void* k,
                   const void* v, void* out, int t, hipStream_t stream)
 {
-    hipLaunchKernelGGL((wkv_step_kernel<TT, D, unroll<TT, D, MAXT>(), MAXT>), dim3(c.units), dim3(threads), lds,
-                       stream, c, q, k, v, out, t);
+    constexpr int U = unroll<TT, D, MAXT>();
+    // with the budget a multiple of the chunk, entry m (the incoming token) would open a chunk of its own
+    if (c.m % ((threads / ROW_LANES) * U) == 0)
+        hipLaunchKernelGGL((wkv_step_kernel<TT, D, U, MAXT, true>), dim3(c.units), dim3(threads), lds,
+                           stream, c, q, k, v, out, t);
+    else
+        hipLaunchKernelGGL((wkv_step_kernel<TT, D, U, MAXT, false>), dim3(c.units), dim3(threads), lds,
+                           stream, c, q, k, v, out, t);
     return hipGetLastError();
 }
 

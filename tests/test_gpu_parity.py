@@ -69,6 +69,19 @@ def test_ragged_tail_lengths():
         _run(cfg, threads=256)
 
 
+@pytest.mark.parametrize("threads", [256, 512, 1024])
+@pytest.mark.parametrize("dtype,d", [("fp16", 128), ("bf16", 64), ("bf16", 256), ("fp32", 64), ("fp32", 128)])
+def test_budgets_that_are_whole_chunks(dtype, d, threads):
+    """Budgets that are a multiple of the rows a workgroup streams per chunk (64..512 rows,
+    depending on row width and workgroup size) take the kernel variant that attends the incoming
+    token outside the chunks.  Window 1 lets the victim's right neighbour be the incoming token."""
+    for m, R, sink in ((128, 1, 0), (512, 1, 0), (512, 9, 2), (1024, 3, 0)):
+        if m + 1 > 4 * threads:
+            continue
+        cfg = synth.StreamConfig(f"chunk{m}", 7350 + m + R, 1, 3, d, dtype, m + 70, m, R)
+        _run(cfg, threads=threads, n_sink=sink)
+
+
 def test_sink_protection_and_eviction_variants():
     cfg = synth.StreamConfig("sink", 7400, 1, 6, 128, "fp16", 260, 48, 8)
     _run(cfg, n_sink=4)
