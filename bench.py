@@ -27,6 +27,7 @@ def parse():
     ap.add_argument("--workload", default="cfg3", choices=["cfg2", "cfg3", "cfg4", "cfg5"])
     ap.add_argument("--layers", type=int, default=0, help="override the number of stacked layers")
     ap.add_argument("--threads", type=int, default=0, help="workgroup size override (256/512/1024)")
+    ap.add_argument("--split", type=int, default=0, help="workgroups per unit override (1/2/4/8/16; 0 = library's choice)")
     ap.add_argument("--skip-cpu-baseline", action="store_true")
     ap.add_argument("--also", default="cfg5", choices=["", "cfg2", "cfg4", "cfg5"],
                     help="second workload measured in the same run and reported under 'also' ('' = none)")
@@ -81,7 +82,7 @@ def main():
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
 
-    def run_workload(name, layers, W, K, threads):
+    def run_workload(name, layers, W, K, threads, split=0):
         """Stage the stream, fill the cache, warm up, time K steps.  Returns the measurements."""
         cfg = synth.CONFIGS[name]
         layers = layers or cfg.layers
@@ -100,7 +101,7 @@ def main():
             bufs.append((tq, tk, tv, out))
             ptrs.append(tuple(x.data_ptr() for x in (tq, tk, tv, out)))
             caches.append(wkv.Cache(cfg.batch, cfg.heads, cfg.head_dim, cfg.budget, cfg.recent, code,
-                                    threads=threads))
+                                    threads=threads, split=split))
         gen_s = time.perf_counter() - t0
         stride = cfg.units * cfg.head_dim * eb
         stream = torch.cuda.current_stream().cuda_stream
@@ -135,7 +136,7 @@ def main():
                     kernel_us=kernel_us, achieved=achieved, tokens_per_s=cfg.batch * K / wall)
 
     W, K = args.warmup, args.steps
-    m = run_workload(args.workload, args.layers, W, K, args.threads)
+    m = run_workload(args.workload, args.layers, W, K, args.threads, args.split)
     cfg, layers, fill = m["cfg"], m["layers"], m["fill"]
 
     def roofline(mm, workload):
@@ -159,6 +160,7 @@ def main():
         "config": {"workload": describe(m, args.workload),
                    "units_per_launch": cfg.units, "launches_per_step": layers,
                    "threads_per_workgroup": args.threads or "auto",
+                   "workgroups_per_unit": args.split or "auto",
                    "input_staging_s": round(m["gen_s"], 1)},
         "roofline": roofline(m, args.workload),
     }

@@ -72,7 +72,9 @@ typedef struct wkv_options {
     int merge_mode;              /* optional: WKV_MERGE_*                                          */
     int log_capacity;            /* optional: steps of eviction log kept (ring), default 1024      */
     int threads;                 /* optional: workgroup size 256/512/1024, default chosen by units */
-    int reserved[5];             /* must be zero                                                   */
+    int split;                   /* optional: workgroups per unit, 1/2/4/8/16; default: 1 unless   */
+                                 /*   the units alone would leave most of the GPU idle             */
+    int reserved[4];             /* must be zero                                                   */
 } wkv_options;
 
 /*
@@ -80,7 +82,9 @@ typedef struct wkv_options {
  * for batch*heads units on the current HIP device.  The library allocates and
  * owns the device memory: per unit `budget` rows of K and V in `dtype`, one
  * fp64 score sum, one int32 original position and one int32 token-order link
- * per slot, plus the eviction log.  The softmax scale is 1/sqrt(head_dim).
+ * per slot, plus the eviction log; with split > 1 also the per-step scratch the
+ * workgroups of a unit exchange (one fp64 per slot and split partial output
+ * rows per unit).  The softmax scale is 1/sqrt(head_dim).
  * *h is written only on success.
  */
 int wkv_create(wkv_handle** h, int batch, int heads, int head_dim,

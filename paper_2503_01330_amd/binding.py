@@ -34,7 +34,7 @@ EXPORTS = ("wkv_create", "wkv_create_ex", "wkv_step", "wkv_state", "wkv_load", "
 class wkv_options(C.Structure):
     _fields_ = [(n, C.c_int) for n in ("batch", "heads", "head_dim", "budget", "recent_window",
                                         "dtype", "n_sink", "score_mode", "merge_mode",
-                                        "log_capacity", "threads")] + [("reserved", C.c_int * 5)]
+                                        "log_capacity", "threads", "split")] + [("reserved", C.c_int * 4)]
 
 
 class WkvError(RuntimeError):
@@ -75,9 +75,9 @@ def wkv_version() -> int:
 
 
 def make_options(batch, heads, head_dim, budget, recent_window, dtype, n_sink=0, score_mode=0,
-                 merge_mode=0, log_capacity=0, threads=0) -> wkv_options:
+                 merge_mode=0, log_capacity=0, threads=0, split=0) -> wkv_options:
     return wkv_options(batch, heads, head_dim, budget, recent_window, dtype, n_sink, score_mode,
-                       merge_mode, log_capacity, threads)
+                       merge_mode, log_capacity, threads, split)
 
 
 def wkv_create(batch, heads, head_dim, budget, recent_window, dtype):

@@ -46,4 +46,26 @@ hipError_t wkv_step_prepare(int dtype, int head_dim, size_t lds);
 // Largest number of attended entries (m + 1) a workgroup of this size handles.
 int wkv_step_max_entries(int threads);
 
+// ---- the variant for few units (wkv_split.hip): S workgroups per unit
+//
+// Device scratch of a handle that splits: what the S slices of a unit hand to the workgroup
+// that finishes the unit.  Rewritten by every step; only cnt carries state (zero between steps).
+struct WkvSplit {
+    double*   lg;        // [units][m+1] exp(logit - maximum of its slice) of every entry of the current step
+    void*     po;        // [units][S][D] per-slice sum of exp(logit - slice maximum) . V; 8 bytes per
+                         //              element are allocated, fp32 is stored for 16-bit caches, fp64 for fp32
+    double*   pm;        // [units][S] slice maximum of the logits (-inf for an empty slice)
+    double*   pl;        // [units][S] per-slice sum of the weights the partial output row was built with
+    double*   pe;        // [units][S] per-slice sum of exp(logit - slice maximum), fp64
+    uint32_t* cnt;       // [units] slices of the unit that have delivered
+    int S;
+};
+
+// Same contract as wkv_launch_step, grid = units * sp.S workgroups.
+hipError_t wkv_launch_split(const WkvCache& c, const WkvSplit& sp, int dtype, int head_dim, int threads,
+                            const void* q, const void* k_new, const void* v_new, void* out,
+                            int64_t t, hipStream_t stream);
+size_t wkv_split_lds_bytes(int m, int dtype, int head_dim, int threads);
+hipError_t wkv_split_prepare(int dtype, int head_dim, size_t lds);
+
 #endif

@@ -37,8 +37,7 @@
 // per-wave results are combined by one DPP row reduction per wave, and the two
 // V rows of the merge are taken from the registers they were streamed into.
 #include "wkv_internal.h"
-
-#include <math.h>
+#include "wkv_device.h"
 
 // Phase markers for an out-of-tree timing harness; they compile to nothing in the library.
 #ifndef WKV_MARK
@@ -46,187 +45,6 @@
 #endif
 
 namespace {
-
-constexpr int ROW_LANES = 16;   // lanes that share one K/V row
-
-struct TF32  { static constexpr int BYTES = 4; using soft_t = double; };
-struct TF16  { static constexpr int BYTES = 2; using soft_t = float;  };
-struct TBF16 { static constexpr int BYTES = 2; using soft_t = float;  };
-
-typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
-
-// ---------------------------------------------------------------- raw row I/O
-template <int NW>
-__device__ __forceinline__ void load_words(const void* p, uint32_t (&w)[NW]) {
-    if constexpr (NW == 2) {
-        uint2 x = *reinterpret_cast<const uint2*>(p);
-        w[0] = x.x; w[1] = x.y;
-    } else {
-#pragma unroll
-        for (int i = 0; i < NW / 4; ++i) {
-            uint4 x = reinterpret_cast<const uint4*>(p)[i];
-            w[4 * i] = x.x; w[4 * i + 1] = x.y; w[4 * i + 2] = x.z; w[4 * i + 3] = x.w;
-        }
-    }
-}
-
-template <int NW>
-__device__ __forceinline__ void store_words(void* p, const uint32_t (&w)[NW]) {
-    if constexpr (NW == 2) {
-        *reinterpret_cast<uint2*>(p) = make_uint2(w[0], w[1]);
-    } else {
-#pragma unroll
-        for (int i = 0; i < NW / 4; ++i)
-            reinterpret_cast<uint4*>(p)[i] = make_uint4(w[4 * i], w[4 * i + 1], w[4 * i + 2], w[4 * i + 3]);
-    }
-}
-
-// storage words -> exact fp32 values
-template <class TT, int EPL, int NW>
-__device__ __forceinline__ void decode(const uint32_t (&w)[NW], float (&x)[EPL]) {
-    if constexpr (TT::BYTES == 4) {
-#pragma unroll
-        for (int e = 0; e < EPL; ++e) x[e] = __builtin_bit_cast(float, w[e]);
-    } else if constexpr (__is_same(TT, TF16)) {
-#pragma unroll
-        for (int i = 0; i < NW; ++i) {
-            half2_t h = __builtin_bit_cast(half2_t, w[i]);
-            x[2 * i] = (float)h.x; x[2 * i + 1] = (float)h.y;
-        }
-    } else {
-#pragma unroll
-        for (int i = 0; i < NW; ++i) {
-            x[2 * i]     = __builtin_bit_cast(float, w[i] << 16);
-            x[2 * i + 1] = __builtin_bit_cast(float, w[i] & 0xFFFF0000u);
-        }
-    }
-}
-
-// one storage element -> fp32 / fp32 -> one storage element (round to nearest even)
-template <class TT> __device__ __forceinline__ float load_elem(const void* base, int idx) {
-    if constexpr (TT::BYTES == 4) return reinterpret_cast<const float*>(base)[idx];
-    else if constexpr (__is_same(TT, TF16)) return (float)reinterpret_cast<const _Float16*>(base)[idx];
-    else return __builtin_bit_cast(float, (uint32_t)reinterpret_cast<const uint16_t*>(base)[idx] << 16);
-}
-
-// one storage element as raw bits (no conversion: nothing waits on the load)
-template <class TT> __device__ __forceinline__ uint32_t load_bits(const void* base, int idx) {
-    if constexpr (TT::BYTES == 4) return reinterpret_cast<const uint32_t*>(base)[idx];
-    else return reinterpret_cast<const uint16_t*>(base)[idx];
-}
-// raw bits of one storage element -> fp32
-template <class TT> __device__ __forceinline__ float bits_elem(uint32_t b) {
-    if constexpr (TT::BYTES == 4) return __builtin_bit_cast(float, b);
-    else if constexpr (__is_same(TT, TF16)) return (float)__builtin_bit_cast(_Float16, (uint16_t)b);
-    else return __builtin_bit_cast(float, b << 16);
-}
-template <class TT> __device__ __forceinline__ void store_bits(void* base, int idx, uint32_t b) {
-    if constexpr (TT::BYTES == 4) reinterpret_cast<uint32_t*>(base)[idx] = b;
-    else reinterpret_cast<uint16_t*>(base)[idx] = (uint16_t)b;
-}
-__device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
-    uint32_t b = __builtin_bit_cast(uint32_t, f);
-    if ((b & 0x7FFFFFFFu) > 0x7F800000u) return (uint16_t)((b >> 16) | 0x40);   // NaN stays NaN
-    return (uint16_t)((b + 0x7FFFu + ((b >> 16) & 1u)) >> 16);
-}
-
-template <class TT> __device__ __forceinline__ void store_elem(void* base, int idx, float f) {
-    if constexpr (TT::BYTES == 4) reinterpret_cast<float*>(base)[idx] = f;
-    else if constexpr (__is_same(TT, TF16)) reinterpret_cast<_Float16*>(base)[idx] = (_Float16)f;
-    else reinterpret_cast<uint16_t*>(base)[idx] = f32_to_bf16_rne(f);
-}
-
-// fp64 -> fp32 with round-to-odd, so that the following fp32 -> 16-bit rounding
-// (nearest even) gives the correctly rounded 16-bit value of the fp64 input.
-__device__ __forceinline__ float f64_to_f32_round_odd(double x) {
-    float f = (float)x;
-    double back = (double)f;
-    if (back != x && __builtin_isfinite(f)) {
-        uint32_t b = __builtin_bit_cast(uint32_t, f);
-        if (fabs(back) > fabs(x)) b -= 1u;   // step to the neighbour nearer zero
-        b |= 1u;                             // inexact: force the odd neighbour
-        f = __builtin_bit_cast(float, b);
-    }
-    return f;
-}
-
-template <class TT> __device__ __forceinline__ void store_elem_f64(void* base, int idx, double x) {
-    if constexpr (TT::BYTES == 4) reinterpret_cast<float*>(base)[idx] = (float)x;
-    else store_elem<TT>(base, idx, f64_to_f32_round_odd(x));
-}
-
-// ------------------------------------------------------------- lane exchange
-template <int CTRL, class X> __device__ __forceinline__ X dpp(X x) {
-    return __builtin_amdgcn_update_dpp(x, x, CTRL, 0xF, 0xF, false);
-}
-
-// Sum over the 16 lanes of a DPP row; every lane ends with the same bits.
-template <class X> __device__ __forceinline__ X row_allsum(X x) {
-    x += dpp<0xB1>(x);    // quad_perm [1,0,3,2]
-    x += dpp<0x4E>(x);    // quad_perm [2,3,0,1]
-    x += dpp<0x141>(x);   // row_half_mirror
-    x += dpp<0x140>(x);   // row_mirror
-    return x;
-}
-
-__device__ __forceinline__ float  soft_exp(float x)  { return __expf(x); }
-__device__ __forceinline__ double soft_exp(double x) { return exp(x); }
-
-// ------------------------------------------------------- wave-level reductions
-// All 64 lanes active.  Results are uniform across the wave and depend only on
-// the data (fixed combination order), never on timing.
-__device__ __forceinline__ double readlane_f64(double x, int l) {
-    const int lo = __builtin_amdgcn_readlane(__double2loint(x), l);
-    const int hi = __builtin_amdgcn_readlane(__double2hiint(x), l);
-    return __hiloint2double(hi, lo);
-}
-
-__device__ __forceinline__ double wave_sum(double x) {
-    x = row_allsum(x);
-    return ((readlane_f64(x, 0) + readlane_f64(x, 16)) + readlane_f64(x, 32)) + readlane_f64(x, 48);
-}
-
-__device__ __forceinline__ int wave_sum(int x) {
-    x = row_allsum(x);
-    return __builtin_amdgcn_readlane(x, 0) + __builtin_amdgcn_readlane(x, 16) +
-           __builtin_amdgcn_readlane(x, 32) + __builtin_amdgcn_readlane(x, 48);
-}
-
-// candidate victim: lexicographic (score, token index), so ties go to the oldest token
-struct Best { double s; int pos; int phys; };
-
-__device__ __forceinline__ bool better(double s, int pos, const Best& b) {
-    return (s < b.s) || (s == b.s && pos < b.pos);
-}
-
-template <int CTRL> __device__ __forceinline__ void best_step(Best& b) {
-    const Best o = { dpp<CTRL>(b.s), dpp<CTRL>(b.pos), dpp<CTRL>(b.phys) };
-    if (better(o.s, o.pos, b)) b = o;
-}
-
-__device__ __forceinline__ Best wave_argmin(Best b) {
-    best_step<0xB1>(b); best_step<0x4E>(b); best_step<0x141>(b); best_step<0x140>(b);
-    Best r = { readlane_f64(b.s, 0), __builtin_amdgcn_readlane(b.pos, 0), __builtin_amdgcn_readlane(b.phys, 0) };
-#pragma unroll
-    for (int l = 16; l < 64; l += 16) {
-        const Best o = { readlane_f64(b.s, l), __builtin_amdgcn_readlane(b.pos, l),
-                         __builtin_amdgcn_readlane(b.phys, l) };
-        if (better(o.s, o.pos, r)) r = o;
-    }
-    return r;
-}
-
-// Combining the per-wave results that sit in LDS arrays of nw <= 16 entries: lane w takes
-// entry w, one DPP row reduction, lane 0 broadcasts.  Every wave does this for itself
-// (a few dozen instructions) instead of every thread scanning the arrays serially.
-__device__ __forceinline__ double combine_max(const double* arr, int nw, int lane) {
-    double x = (lane < nw) ? arr[lane] : -INFINITY;
-    x = fmax(x, dpp<0xB1>(x)); x = fmax(x, dpp<0x4E>(x)); x = fmax(x, dpp<0x141>(x)); x = fmax(x, dpp<0x140>(x));
-    return readlane_f64(x, 0);
-}
-
-constexpr int MAXPT = 4;       // entries whose a/pos one thread fetches ahead of the streaming loop
-constexpr int NONE_POS = 0x7FFFFFFF;
 
 // ------------------------------------------------------------------ the kernel
 // Entries attended in step t: the Lc = min(t, m) cached slots, then the incoming
@@ -621,15 +439,6 @@ void wkv_step_kernel(WkvCache c, const void* __restrict__ q_, const void* __rest
         c.log_slot[row] = (compress && sane) ? bk_i[4] : -1;
     }
     WKV_MARK(7);
-}
-
-// Rows per 16-lane group requested per streaming chunk, sized so that one chunk of K and
-// one of V (both raw, in registers) fit the register file: 128 VGPRs per thread for a
-// 1024-thread workgroup, 256 for 512 threads or fewer.
-template <class TT, int D, int MAXT> constexpr int unroll() {
-    constexpr int words = D / ROW_LANES * TT::BYTES / 4;     // registers per row per lane
-    if (MAXT > 512) return words <= 2 ? 8 : words == 4 ? 4 : 2;
-    return words <= 4 ? 8 : 4;
 }
 
 template <class TT, int D, int MAXT>

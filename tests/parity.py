@@ -53,6 +53,9 @@ def gpu_stream(cfg, layer=0, units_sel=None, steps=None, progress=None, **create
     selected units as exact fp32)."""
     steps = cfg.steps if steps is None else steps
     st = synth.Stream(cfg, layer)
+    # one workgroup per unit unless a test asks otherwise (split=0 lets the library choose, as
+    # the benchmark does; split>1 takes the sliced kernel)
+    create_kw.setdefault("split", 1)
     cache = wkv.Cache(cfg.batch, cfg.heads, cfg.head_dim, cfg.budget, cfg.recent,
                       synth.DTYPE_CODE[cfg.dtype], **create_kw)
     sel = np.arange(cfg.units) if units_sel is None else np.asarray(units_sel)

@@ -41,7 +41,8 @@ def test_options_struct_layout():
     (dict(n_sink=-1), wkv.WKV_EINVAL), (dict(n_sink=60, recent_window=16), wkv.WKV_EINVAL),
     (dict(score_mode=3), wkv.WKV_EINVAL), (dict(merge_mode=2), wkv.WKV_EINVAL),
     (dict(score_mode=1, merge_mode=0), wkv.WKV_EINVAL), (dict(threads=128), wkv.WKV_EINVAL),
-    (dict(log_capacity=-5), wkv.WKV_EINVAL),
+    (dict(log_capacity=-5), wkv.WKV_EINVAL), (dict(split=3), wkv.WKV_EINVAL), (dict(split=32), wkv.WKV_EINVAL),
+    (dict(split=-1), wkv.WKV_EINVAL),
 ])
 def test_invalid_options_are_rejected_before_touching_the_gpu(kw, code):
     base = dict(batch=1, heads=4, head_dim=64, budget=64, recent_window=16, dtype=wkv.WKV_FP32)
@@ -68,3 +69,18 @@ def test_size_arithmetic():
     assert wkv.wkv_step_bytes(opt) == units * (L * (2 * row + 20) + 7 * row)
     kv = 2 * units * L * row
     assert kv < wkv.wkv_workspace_bytes(opt) < kv * 1.1 + (1 << 22)
+
+
+def test_workgroups_per_unit_are_chosen_by_shape():
+    """Host-only: the scratch of the sliced kernel shows in the workspace size.  One sequence
+    of a 32-head model with 819 slots is cut into 4 slices per unit by default; 256 units are
+    not cut; short score rows are not cut; an explicit request wins."""
+    def ws(batch, heads, m, **kw):
+        return wkv.wkv_workspace_bytes(wkv.make_options(batch, heads, 128, m, 32, wkv.WKV_FP16, **kw))
+    def scratch(units, m, S):     # exponentials per slot + S partial rows (8-byte cells) + 3 values per slice + counter
+        return units * ((m + 1) * 8 + S * 128 * 8 + 3 * S * 8 + 4)
+    assert ws(1, 32, 819) == ws(1, 32, 819, split=1) + scratch(32, 819, 4)
+    assert ws(1, 32, 819, split=16) == ws(1, 32, 819, split=1) + scratch(32, 819, 16)
+    assert ws(8, 32, 410) == ws(8, 32, 410, split=1)
+    assert ws(1, 32, 256) == ws(1, 32, 256, split=1)
+    assert ws(4, 32, 2048) == ws(4, 32, 2048, split=1) + scratch(128, 2048, 2)

@@ -82,6 +82,56 @@ def test_budgets_that_are_whole_chunks(dtype, d, threads):
         _run(cfg, threads=threads, n_sink=sink)
 
 
+# ---- the sliced kernel (several workgroups per unit, for caches with few units)
+@pytest.mark.parametrize("split", [2, 4, 8, 16])
+def test_sliced_units_small_shapes(split):
+    """Every slice count against the oracle: slices that are empty while the cache fills (and for
+    good with a single-slot budget), ragged slices, window 1, sinks, every dtype and row width."""
+    _run(synth.scaled(synth.CONFIGS["cfg1"], steps=300), split=split)
+    for m, R in ((1, 1), (2, 2), (33, 1), (100, 17), (257, 3)):
+        _run(synth.StreamConfig(f"s{split}m{m}", 7600 + m, 1, 3, 128, "fp16", m + 90, m, R), split=split)
+    _run(synth.StreamConfig("s-bf16-64", 7610, 2, 2, 64, "bf16", 260, 150, 5), split=split)
+    _run(synth.StreamConfig("s-bf16-256", 7611, 1, 2, 256, "bf16", 260, 150, 5), split=split, n_sink=3)
+    _run(synth.StreamConfig("s-fp32-128", 7612, 1, 2, 128, "fp32", 260, 150, 5), split=split)
+    _run(synth.StreamConfig("s-fill", 7613, 1, 2, 128, "fp16", 120, 200, 8), split=split)
+    cfg = synth.StreamConfig("s-evict", 7614, 1, 4, 128, "fp16", 200, 48, 8)
+    _run(cfg, split=split, merge_mode=wkv.WKV_MERGE_NONE)
+    _run(cfg, split=split, merge_mode=wkv.WKV_MERGE_NONE, score_mode=wkv.WKV_SCORE_LAST)
+
+
+@pytest.mark.parametrize("threads", [256, 512, 1024])
+def test_sliced_units_all_workgroup_sizes(threads):
+    _run(synth.StreamConfig("s-thr", 7620 + threads, 1, 3, 128, "fp16", 700, 600, 9), split=4, threads=threads)
+
+
+def test_sliced_units_cfg2_as_the_library_chooses():
+    """One sequence of a 32-head model: the library itself picks the sliced kernel here
+    (its scratch shows in the workspace size), full 4096-token stream, every unit."""
+    cfg = synth.CONFIGS["cfg2"]
+    code = synth.DTYPE_CODE[cfg.dtype]
+    auto = wkv.wkv_workspace_bytes(wkv.make_options(cfg.batch, cfg.heads, cfg.head_dim, cfg.budget, cfg.recent, code))
+    one = wkv.wkv_workspace_bytes(wkv.make_options(cfg.batch, cfg.heads, cfg.head_dim, cfg.budget, cfg.recent, code,
+                                                   split=1))
+    assert auto > one
+    stats = _run(cfg, label="cfg2 sliced", split=0)
+    assert stats["near_ties"] == 0
+
+
+def test_sliced_units_maximum_budget_and_determinism():
+    m = wkv.WKV_MAX_BUDGET
+    cfg = synth.StreamConfig("s-max", 7630, 1, 2, 128, "fp16", m + 40, m, 1)
+    _run(cfg, label="max budget sliced", split=8)
+    cfg = synth.scaled(synth.CONFIGS["cfg2"], steps=900, heads=4, budget=300)
+    a = parity.gpu_stream(cfg, split=8); b = parity.gpu_stream(cfg, split=8)
+    try:     # which workgroup finishes a unit varies from run to run; the result must not
+        assert np.array_equal(a["evict_pos"], b["evict_pos"])
+        assert np.array_equal(a["out"], b["out"])
+        assert np.array_equal(a["cache"].state(wkv.WKV_V), b["cache"].state(wkv.WKV_V))
+        assert np.array_equal(a["cache"].state(wkv.WKV_SCORE_SUM), b["cache"].state(wkv.WKV_SCORE_SUM))
+    finally:
+        a["cache"].close(); b["cache"].close()
+
+
 def test_sink_protection_and_eviction_variants():
     cfg = synth.StreamConfig("sink", 7400, 1, 6, 128, "fp16", 260, 48, 8)
     _run(cfg, n_sink=4)
@@ -113,14 +163,14 @@ def test_cfg3_stack_sampled_layers_and_units():
     cfg = synth.CONFIGS["cfg3"]
     for layer in (0, 31):
         sel = np.random.default_rng(layer).choice(cfg.units, 6, replace=False)
-        stats = _run(cfg, units_sel=np.sort(sel), layer=layer, label=f"cfg3 layer {layer}")
+        stats = _run(cfg, units_sel=np.sort(sel), layer=layer, label=f"cfg3 layer {layer}", split=0)
         assert stats["near_ties"] == 0
 
 
 def test_cfg4_long_stream_sampled_units():
     cfg = synth.CONFIGS["cfg4"]
     sel = np.array([0, 37, 90, 127])
-    g = parity.gpu_stream(cfg, units_sel=sel, progress="cfg4")
+    g = parity.gpu_stream(cfg, units_sel=sel, progress="cfg4", split=0)   # as benchmarked: 2 workgroups per unit
     try:
         stats = parity.compare(cfg, g)
         pos = g["cache"].state(wkv.WKV_POS)
@@ -134,7 +184,7 @@ def test_cfg4_long_stream_sampled_units():
 def test_cfg5_batched_bf16_sampled_units():
     cfg = synth.CONFIGS["cfg5"]
     sel = np.sort(np.random.default_rng(5).choice(cfg.units, 8, replace=False))
-    _run(cfg, units_sel=sel, label="cfg5")
+    _run(cfg, units_sel=sel, label="cfg5", split=0)
 
 
 def test_maximum_budget_uses_the_large_lds_path():
@@ -192,7 +242,8 @@ def test_host_side_argument_checks_with_a_live_handle():
 
 def test_randomised_shapes():
     """Many small random configurations (budget, window, sinks, rule variants, head size, dtype,
-    workgroup size, unit count), each streamed past its fill phase and compared in full."""
+    workgroup size, workgroups per unit, unit count), each streamed past its fill phase and
+    compared in full."""
     g = np.random.default_rng(20250301)
     ran = 0
     for case in range(40):
@@ -220,6 +271,8 @@ def test_randomised_shapes():
         steps = m + int(g.integers(5, 60))
         cfg = synth.StreamConfig(f"rand{case}", 9000 + case, batch, heads, d, dtype, steps, m, R,
                                  key_rank=int(g.integers(2, 17)), key_noise=float(g.random() < 0.5) * 0.1)
+        # drawn last so that the shapes above stay what they were: workgroups per unit
+        kw["split"] = [1, 1, 0, 2, 4, 8, 16][case % 7]
         _run(cfg, **kw)
         ran += 1
     assert ran == 40
