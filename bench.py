@@ -126,13 +126,17 @@ def main():
         wall = time.perf_counter() - w0
         ev_ms = ev0.elapsed_time(ev1)
         step_bytes = caches[0].step_bytes()              # algorithmic bytes of one launch
+        # which kernel the library launches for this shape: the sliced one allocates scratch
+        o = caches[0].opt
+        one = wkv.make_options(o.batch, o.heads, o.head_dim, o.budget, o.recent_window, o.dtype, split=1)
+        kernel = "wkv_split_kernel" if wkv.wkv_workspace_bytes(o) > wkv.wkv_workspace_bytes(one) else "wkv_step_kernel"
         for c in caches:
             c.close()
         del bufs
         torch.cuda.empty_cache()
         kernel_us = ev_ms * 1e3 / (K * layers)            # average launch duration incl. gaps (HIP events)
         achieved = step_bytes / (kernel_us * 1e-6) / 1e9
-        return dict(cfg=cfg, layers=layers, fill=fill, wall=wall, gen_s=gen_s, step_bytes=step_bytes,
+        return dict(cfg=cfg, layers=layers, fill=fill, wall=wall, gen_s=gen_s, step_bytes=step_bytes, kernel=kernel,
                     kernel_us=kernel_us, achieved=achieved, tokens_per_s=cfg.batch * K / wall)
 
     W, K = args.warmup, args.steps
@@ -142,7 +146,7 @@ def main():
     def roofline(mm, workload):
         return {"bound": "hbm", "achieved": round(mm["achieved"], 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(mm["achieved"] / HBM_PEAK_GBS, 4), "traffic": measured_traffic(workload),
-                "kernel": "wkv_step_kernel", "bytes_per_launch": mm["step_bytes"],
+                "kernel": mm["kernel"], "bytes_per_launch": mm["step_bytes"],
                 "avg_launch_us": round(mm["kernel_us"], 3)}
 
     def describe(mm, workload):

@@ -89,21 +89,6 @@ void wkv_split_kernel(WkvCache c, WkvSplit sp, const void* __restrict__ q_, cons
     // =========================================================== phase A: the slice
     uint32_t qw[NW32];
     load_words<NW32>(qu + sub * LANEB, qw);
-    // What phase B needs from the previous step (score sums, token indices, links; one entry per
-    // thread and round, MAXPT * NT >= L is checked on the host) is requested now by every
-    // workgroup, although only the finishing one uses it: the request costs little, and waiting
-    // for it after the ticket would put another memory round trip on the critical path.
-    double a_reg[MAXPT];
-    int pos_reg[MAXPT], nxt_reg[MAXPT];
-#pragma unroll
-    for (int k = 0; k < MAXPT; ++k) {
-        const int i = tid + k * NT;
-        const int ic = (i < Lc) ? i : 0;
-        a_reg[k] = au[ic];
-        pos_reg[k] = pu[ic];
-        nxt_reg[k] = nu[ic];
-    }
-
     // Chunk ch of the slice: entries lo + gid + ch*CH + uu*NG, uu < U.  Entry Lc is the incoming
     // token, read from the caller's buffers.  Out-of-range groups re-read a valid row.
     uint32_t kw[U][NW32], vw[U][NW32];
@@ -235,11 +220,19 @@ void wkv_split_kernel(WkvCache c, WkvSplit sp, const void* __restrict__ q_, cons
     if (misc[0] != NS - 1) return;                         // uniform: somebody else finishes this unit
 
     // =========================================================== phase B: the whole score row
-    // the exponentials of every entry, relative to the maximum of the slice that produced them
+    // one entry per thread and round (MAXPT * NT >= L is checked on the host): its exponential,
+    // relative to the maximum of the slice that produced it, and what the previous step left for
+    // it (score sum, token index, link).  Only the finishing workgroup reads these.
+    double a_reg[MAXPT];
+    int pos_reg[MAXPT], nxt_reg[MAXPT];
 #pragma unroll
     for (int k = 0; k < MAXPT; ++k) {
         const int i = tid + k * NT;
+        const int ic = (i < Lc) ? i : 0;
         e_reg[k] = load_agent(&lgu[(i < L) ? i : 0]);
+        a_reg[k] = au[ic];
+        pos_reg[k] = pu[ic];
+        nxt_reg[k] = nu[ic];
     }
     // ... and the partial output rows, requested now so that they arrive while the scores are ranked
     S po_reg[16];
