@@ -41,6 +41,8 @@ def lib():
         L.orc_destroy.argtypes = [C.c_void_p]
         L.orc_run.restype = C.c_int
         L.orc_run.argtypes = [C.c_void_p, C.c_int, fp, fp, fp, dp, ip, ip, dp, dp, ip, dp, C.c_int]
+        L.orc_prefill.restype = C.c_int
+        L.orc_prefill.argtypes = [C.c_void_p, C.c_int, fp, fp, fp, dp, ip, dp, dp, C.c_int]
         L.orc_len.restype = C.c_int
         L.orc_len.argtypes = [C.c_void_p, C.c_int]
         L.orc_tokens.restype = C.c_int64
@@ -105,6 +107,29 @@ class Oracle:
             raise RuntimeError(f"oracle: forced token is not a candidate at local step {-rc - 1}")
         return dict(out=out, evict_slot=es, evict_pos=ep, evict_score=sc, runner_up=ru,
                     forced_score=fs)
+
+    def prefill(self, q, k, v, want_out=True, threads=0):
+        """Bulk prefill of the (empty) cache with a prompt: q,k,v float32 [P, units, d].  Returns
+        out [P,units,d] f64 and the removed tokens in order: evict_pos [max(P-m,0), units] i32,
+        evict_score and runner_up (f64)."""
+        q = np.ascontiguousarray(q, dtype=np.float32)
+        k = np.ascontiguousarray(k, dtype=np.float32)
+        v = np.ascontiguousarray(v, dtype=np.float32)
+        P = q.shape[0]
+        assert q.shape == k.shape == v.shape == (P, self.units, self.d)
+        out = np.empty((P, self.units, self.d), np.float64) if want_out else None
+        ne = max(P - self.m, 0)
+        ep = np.empty((ne, self.units), np.int32)
+        sc = np.empty((ne, self.units), np.float64)
+        ru = np.empty((ne, self.units), np.float64)
+        rc = lib().orc_prefill(self._h, P, _p(q, C.c_float), _p(k, C.c_float), _p(v, C.c_float),
+                               _p(out, C.c_double), _p(ep, C.c_int32), _p(sc, C.c_double),
+                               _p(ru, C.c_double), threads)
+        if rc == -1:
+            raise RuntimeError("oracle: prefill needs an empty cache")
+        if rc == -2:
+            raise ValueError("oracle: the last-step scoring rule is not defined for a prompt")
+        return dict(out=out, evict_pos=ep, evict_score=sc, runner_up=ru)
 
     def length(self, unit=0):
         return lib().orc_len(self._h, unit)

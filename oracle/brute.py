@@ -69,3 +69,42 @@ class BruteUnit:
                 del lst[j]
         self.t += 1
         return o, ev_slot, ev_pos
+
+    def prefill(self, Q, Kp, Vp):
+        """Bulk prefill of the empty cache with a prompt (lists of d-lists).  Reading (the paper
+        has no such procedure): causal attention over the uncompressed prompt, the scores that
+        Algorithm 1's bookkeeping would accumulate over those rows, then selection and merge
+        repeated until m entries remain, with no attention in between.
+        Returns (outputs, removed tokens in order)."""
+        assert self.t == 0
+        d, P = self.d, len(Q)
+        outs = []
+        for t in range(P):
+            self.K.append(list(Kp[t])); self.V.append(list(Vp[t]))
+            self.pos.append(t); self.nmerged.append(1)
+            s = [sum(Q[t][c] * self.K[i][c] for c in range(d)) / math.sqrt(d) for i in range(t + 1)]
+            mx = max(s)
+            e = [math.exp(x - mx) for x in s]
+            S = sum(e)
+            A = [x / S for x in e]
+            outs.append([sum(A[i] * self.V[i][c] for i in range(t + 1)) for c in range(d)])
+            self.a = [x + y for x, y in zip(self.a + [0.0], A)]
+            self.n = [x + 1 for x in self.n + [0]]
+        removed = []
+        while len(self.K) > self.m:
+            L = len(self.K)
+            abar = [self.a[i] / self.n[i] for i in range(L)]
+            j = min(range(self.n_sink, L - self.R), key=lambda i: (abar[i], i))
+            if self.merge:
+                den = abar[j] + abar[j + 1]
+                merged = [(abar[j] * self.V[j][c] + abar[j + 1] * self.V[j + 1][c]) / den if den > 0
+                          else 0.5 * self.V[j][c] + 0.5 * self.V[j + 1][c] for c in range(d)]
+                if self.rounder is not None:
+                    merged = [self.rounder(x) for x in merged]
+                self.V[j + 1] = merged
+                self.nmerged[j + 1] += self.nmerged[j]
+            removed.append(self.pos[j])
+            for lst in (self.K, self.V, self.a, self.n, self.pos, self.nmerged):
+                del lst[j]
+        self.t = P
+        return outs, removed

@@ -16,7 +16,10 @@
  * invariants, a separately written list simulator).  Parity unpinned: only what no
  * implementation-free fact covers -- how close the compressed cache stays to full
  * attention (the paper's evidence is perplexity on data that is not available), and the
- * two eviction-rule variants beyond the special cases tested.
+ * two eviction-rule variants beyond the special cases tested.  The bulk prefill
+ * (orc_prefill) is a reading, not the paper's procedure; it is pinned to causal library
+ * attention, to the streaming path where the two must coincide (P <= m + 1), to the list
+ * simulator, and to the sorted-score consequence of its fixed scores.
  *
  * It shares no code with the HIP library and nothing on the product path may
  * link or call it; only tests, the smoke check and the benchmark's
@@ -287,6 +290,88 @@ int orc_run(orc_t *o, int nsteps, const float *q, const float *k, const float *v
         }
     }
     return bad;
+}
+
+/* ---- bulk prefill -----------------------------------------------------------
+ * The paper streams from an empty cache (Algorithm 1) and says nothing about a prompt that is
+ * given at once.  Reading taken here: the P prompt tokens attend causally to each other over
+ * the UNcompressed prompt (row t is softmax attention of q_t over tokens 0..t, Section III-A);
+ * the score list is what Algorithm 1's bookkeeping accumulates over those rows, a_i = sum_t
+ * A_t[i], n_i = P - i (rows that attended token i); then, while more than m entries remain,
+ * the selection and merge of Algorithm 1 are repeated with those scores (no new attention
+ * between two merges; the survivor keeps its own a and n, so every abar is fixed).  This is
+ * NOT the same function as feeding the prompt token by token, where every token beyond the
+ * m-th attends to an already compressed cache; the two coincide for P <= m + 1.
+ *
+ * Only on an empty cache.  q,k,v: [P][units][d]; out: [P][units][d] or NULL.  ev_pos,
+ * ev_score, runner_up: [max(P-m,0)][units] or NULL -- the tokens removed, in order.
+ * The last-step scoring rule has no meaning for a prompt (which step?): returns -2.
+ * Returns 0, -1 if the cache is not empty. */
+int orc_prefill(orc_t *o, int P, const float *q, const float *k, const float *v, double *out,
+                int32_t *ev_pos, double *ev_score, double *runner_up, int threads)
+{
+    int d = o->d, U = o->units, m = o->m;
+    if (o->score_mode == 2) return -2;
+    for (int iu = 0; iu < U; ++iu) if (o->u[iu].t != 0) return -1;
+    if (P <= 0) return 0;
+#ifdef _OPENMP
+    if (threads <= 0) threads = omp_get_max_threads();
+#pragma omp parallel for schedule(dynamic, 1) num_threads(threads)
+#endif
+    for (int iu = 0; iu < U; ++iu) {
+        unit_t *u = &o->u[iu];
+        double *K = malloc(sizeof(double) * (size_t)P * d), *V = malloc(sizeof(double) * (size_t)P * d);
+        double *a = calloc((size_t)P, sizeof(double)), *s = malloc(sizeof(double) * P), *p = malloc(sizeof(double) * P);
+        double *score = malloc(sizeof(double) * P);
+        int64_t *n = malloc(sizeof(int64_t) * P);
+        int32_t *idx = malloc(sizeof(int32_t) * P), *nm = malloc(sizeof(int32_t) * P);
+        double qd[d], obuf[d];
+        for (int t = 0; t < P; ++t)
+            for (int c = 0; c < d; ++c) {
+                K[(size_t)t * d + c] = (double)k[((size_t)t * U + iu) * d + c];
+                V[(size_t)t * d + c] = (double)v[((size_t)t * U + iu) * d + c];
+            }
+        /* rows of the prompt: A_t over tokens 0..t, o_t = A_t^T V, a += A_t   (Section III-A, Algorithm 1) */
+        for (int t = 0; t < P; ++t) {
+            for (int c = 0; c < d; ++c) qd[c] = (double)q[((size_t)t * U + iu) * d + c];
+            orc_attend(t + 1, d, qd, K, V, s, p, obuf);
+            if (out) memcpy(out + ((size_t)t * U + iu) * d, obuf, sizeof(double) * d);
+            for (int i = 0; i <= t; ++i) a[i] += p[i];
+        }
+        int L = P;
+        for (int i = 0; i < P; ++i) { n[i] = P - i; idx[i] = i; nm[i] = 1; }
+        /* P - m times: least important candidate folds into its right neighbour and is removed.
+         * idx[] lists the remaining tokens oldest first; a, n, nm are kept aligned with it; the
+         * rows of K and V stay where they are (row idx[i]), V rows are rewritten in place. */
+        for (int e = 0; L > m; ++e) {
+            for (int i = 0; i < L; ++i)
+                score[i] = (o->score_mode == 0) ? a[i] / (double)n[i] : a[i];
+            double second;
+            int j = orc_select(score, o->n_sink, L - o->R, &second);
+            if (ev_pos) ev_pos[(size_t)e * U + iu] = idx[j];
+            if (ev_score) ev_score[(size_t)e * U + iu] = score[j];
+            if (runner_up) runner_up[(size_t)e * U + iu] = second;
+            if (o->merge_mode == 0) {
+                double *Vj = V + (size_t)idx[j] * d, *Vr = V + (size_t)idx[j + 1] * d;
+                orc_merge_pair(score[j], score[j + 1], Vj, Vr, d, o->storage, Vr);
+                nm[j + 1] += nm[j];
+            }
+            int tail = L - 1 - j;
+            memmove(idx + j, idx + j + 1, sizeof(int32_t) * tail);
+            memmove(a + j, a + j + 1, sizeof(double) * tail);
+            memmove(n + j, n + j + 1, sizeof(int64_t) * tail);
+            memmove(nm + j, nm + j + 1, sizeof(int32_t) * tail);
+            L -= 1;
+        }
+        for (int i = 0; i < L; ++i) {
+            memcpy(u->K + (size_t)i * d, K + (size_t)idx[i] * d, sizeof(double) * d);
+            memcpy(u->V + (size_t)i * d, V + (size_t)idx[i] * d, sizeof(double) * d);
+            u->a[i] = a[i]; u->n[i] = n[i]; u->pos[i] = idx[i]; u->nmerged[i] = nm[i];
+        }
+        u->L = L; u->t = P;
+        free(K); free(V); free(a); free(s); free(p); free(score); free(n); free(idx); free(nm);
+    }
+    return 0;
 }
 
 int orc_len(const orc_t *o, int unit) { return o->u[unit].L; }

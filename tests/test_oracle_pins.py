@@ -438,3 +438,134 @@ def test_ideal_merge_leaves_the_output_unchanged(t, d):
     if t > 2:
         o_approx, _ = oracle.attend(q, K[1:], np.vstack([approx[None], V[2:]]))
         assert not np.allclose(o_approx, o_full, rtol=1e-9, atol=1e-12)
+
+
+# ---------------------------------------------------------------------------
+# bulk prefill (a reading: the paper only streams; see the oracle's comment)
+# ---------------------------------------------------------------------------
+def _prompt(seed, P, units, d, dtype=np.float16):
+    g = rng(seed)
+    return tuple(g.standard_normal((P, units, d)).astype(dtype).astype(np.float32) for _ in range(3))
+
+
+@pytest.mark.parametrize("P,m", [(1, 4), (7, 7), (12, 20), (21, 20)])
+def test_prefill_equals_streaming_while_nothing_or_one_token_is_evicted(P, m):
+    """For P <= m nothing is compressed; for P = m + 1 the single compression comes after the last
+    row's attention in both procedures.  There the bulk reading and Algorithm 1 must agree."""
+    q, k, v = _prompt(40 + P, P, 3, 16)
+    a = oracle.Oracle(3, 16, m, 2, "fp16"); b = oracle.Oracle(3, 16, m, 2, "fp16")
+    ra = a.prefill(q, k, v); rb = b.run(q, k, v)
+    np.testing.assert_allclose(ra["out"], rb["out"], rtol=0, atol=1e-13)
+    if P > m:
+        assert np.array_equal(ra["evict_pos"][0], rb["evict_pos"][-1])
+    for u in range(3):
+        sa, sb = a.state(u), b.state(u)
+        assert a.tokens(u) == b.tokens(u) == P
+        for key in ("pos", "n", "nmerged"):
+            assert np.array_equal(sa[key], sb[key]), key
+        np.testing.assert_allclose(sa["a"], sb["a"], rtol=1e-13)
+        np.testing.assert_allclose(sa["V"], sb["V"], rtol=0, atol=1e-13)
+        assert np.array_equal(sa["K"], sb["K"])
+
+
+def test_prefill_rows_are_causal_library_attention_and_scores_are_its_column_sums():
+    P, d, m = 37, 32, 64
+    q, k, v = _prompt(51, P, 1, d, np.float32)
+    o = oracle.Oracle(1, d, m, 1)
+    r = o.prefill(q, k, v)
+    S = (q[:, 0].astype(np.float64) @ k[:, 0].astype(np.float64).T) / math.sqrt(d)
+    S[np.triu_indices(P, 1)] = -np.inf
+    A = scipy.special.softmax(S, axis=1)
+    np.testing.assert_allclose(r["out"][:, 0], A @ v[:, 0].astype(np.float64), rtol=0, atol=1e-12)
+    st = o.state(0)
+    np.testing.assert_allclose(st["a"], A.sum(axis=0), rtol=1e-12)
+    assert math.isclose(st["a"].sum(), P, rel_tol=1e-12)            # every row sums to one
+    assert np.array_equal(st["n"], P - np.arange(P))                 # rows that attended token i
+    assert r["evict_pos"].shape == (0, 1)
+
+
+@pytest.mark.parametrize("seed,P,m,R,sink,storage", [(0, 30, 8, 2, 0, "fp64"), (1, 45, 11, 1, 0, "fp16"),
+                                                      (2, 64, 16, 5, 3, "bf16"), (3, 25, 24, 24, 0, "fp64"),
+                                                      (4, 50, 3, 1, 2, "fp16")])
+def test_prefill_equals_list_simulator(seed, P, m, R, sink, storage):
+    d = 8
+    q, k, v = _prompt(60 + seed, P, 1, d)
+    o = oracle.Oracle(1, d, m, R, storage, n_sink=sink)
+    r = o.prefill(q, k, v)
+    rounder = None if storage == "fp64" else (lambda x: oracle.round_storage(x, storage))
+    b = BruteUnit(d, m, R, n_sink=sink, rounder=rounder)
+    outs, removed = b.prefill(q[:, 0].tolist(), k[:, 0].tolist(), v[:, 0].tolist())
+    assert r["evict_pos"][:, 0].tolist() == removed
+    np.testing.assert_allclose(r["out"][:, 0], np.array(outs), rtol=0, atol=1e-12)
+    st = o.state(0)
+    assert st["pos"].tolist() == b.pos and st["nmerged"].tolist() == b.nmerged and st["n"].tolist() == b.n
+    np.testing.assert_allclose(st["a"], b.a, rtol=1e-12)
+    np.testing.assert_allclose(st["V"], np.array(b.V), rtol=0, atol=1e-12)
+
+
+def test_prefill_removes_the_lowest_average_scores_in_ascending_order():
+    """Scores do not change between two merges (the survivor keeps its own a and n), and neither
+    does the protected set, so the removed tokens are exactly the P - m unprotected tokens with the
+    smallest (abar, token) and they leave in that order."""
+    P, d, m, R, sink = 90, 16, 20, 6, 2
+    q, k, v = _prompt(71, P, 2, d)
+    full = oracle.Oracle(2, d, P, 1); full.prefill(q, k, v)
+    o = oracle.Oracle(2, d, m, R, n_sink=sink)
+    r = o.prefill(q, k, v)
+    for u in range(2):
+        st = full.state(u)
+        abar = st["a"] / st["n"]
+        cand = [i for i in range(sink, P - R)]
+        expect = sorted(cand, key=lambda i: (abar[i], i))[: P - m]
+        assert r["evict_pos"][:, u].tolist() == expect
+        assert np.all(np.diff(r["evict_score"][:, u]) >= 0)
+        kept = o.state(u)
+        assert sorted(set(range(P)) - set(expect)) == kept["pos"].tolist()
+        assert kept["nmerged"].sum() == P                              # every raw value sits in exactly one slot
+        assert np.array_equal(kept["n"], P - kept["pos"])
+        np.testing.assert_allclose(kept["a"], st["a"][kept["pos"]], rtol=1e-13)   # survivors keep their own sums
+
+
+def test_prefill_without_merging_keeps_the_survivors_values_and_merging_stays_in_the_hull():
+    P, d, m = 40, 8, 10
+    q, k, v = _prompt(81, P, 1, d)
+    ev = oracle.Oracle(1, d, m, 2, merge_mode=1); ev.prefill(q, k, v)
+    st = ev.state(0)
+    assert np.array_equal(st["V"], v[st["pos"], 0].astype(np.float64))
+    assert np.all(st["nmerged"] == 1)
+    mg = oracle.Oracle(1, d, m, 2); mg.prefill(q, k, v)
+    sm = mg.state(0)
+    assert np.array_equal(sm["pos"], st["pos"])                        # same selection, values differ
+    lo = 0
+    for slot, p_ in enumerate(sm["pos"]):
+        block = v[lo:p_ + 1, 0].astype(np.float64)                     # the run of tokens folded into this slot
+        assert np.all(sm["V"][slot] >= block.min(axis=0) - 1e-12) and np.all(sm["V"][slot] <= block.max(axis=0) + 1e-12)
+        assert sm["nmerged"][slot] == p_ + 1 - lo
+        lo = p_ + 1
+
+
+def test_prefill_refuses_a_used_cache_and_the_last_step_rule():
+    q, k, v = _prompt(91, 5, 1, 8)
+    o = oracle.Oracle(1, 8, 4, 1)
+    o.run(q[:1], k[:1], v[:1])
+    with pytest.raises(RuntimeError):
+        o.prefill(q, k, v)
+    with pytest.raises(ValueError):
+        oracle.Oracle(1, 8, 4, 1, score_mode=2, merge_mode=1).prefill(q, k, v)
+
+
+def test_streaming_after_prefill_continues_from_the_prefilled_state():
+    """A decode step after the prompt sees the compressed cache with the prompt's score sums and
+    counts: compare with the list simulator doing the same two calls."""
+    P, d, m, R = 30, 8, 12, 3
+    q, k, v = _prompt(95, P + 6, 1, d)
+    o = oracle.Oracle(1, d, m, R, "fp16")
+    o.prefill(q[:P], k[:P], v[:P])
+    r = o.run(q[P:], k[P:], v[P:])
+    b = BruteUnit(d, m, R, rounder=lambda x: oracle.round_storage(x, "fp16"))
+    b.prefill(q[:P, 0].tolist(), k[:P, 0].tolist(), v[:P, 0].tolist())
+    for t in range(P, P + 6):
+        ob, _, ep = b.step(q[t, 0].tolist(), k[t, 0].tolist(), v[t, 0].tolist())
+        np.testing.assert_allclose(r["out"][t - P, 0], ob, rtol=0, atol=1e-12)
+        assert r["evict_pos"][t - P, 0] == ep
+    assert o.state(0)["pos"].tolist() == b.pos and o.state(0)["n"].tolist() == b.n
