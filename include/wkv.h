@@ -50,6 +50,7 @@ extern "C" {
 
 /* limits of this build */
 #define WKV_MAX_BUDGET 4095   /* slots per unit, bounded by the LDS staging of one score row */
+#define WKV_MAX_PROMPT 8192   /* tokens wkv_prefill takes at once, bounded by the LDS staging of their scores */
 
 /* which entries may be ranked / how the victim's value is treated (wkv_options) */
 #define WKV_SCORE_AVERAGE    0   /* abar = a / n: WeightedKV (Algorithm 1)                         */
@@ -110,6 +111,29 @@ int wkv_create_ex(wkv_handle** h, const wkv_options* opt);
  */
 int wkv_step(wkv_handle* h, const void* q, const void* k_new, const void* v_new,
              void* out, void* stream);
+
+/*
+ * Bulk prefill of an EMPTY cache with a prompt of n_tokens tokens.  The paper streams from an
+ * empty cache (Algorithm 1) and has no procedure for a prompt; what this call computes:
+ *   - out[t] = softmax(q_t^T K_{0..t} / sqrt(d)) V_{0..t} over the UNcompressed prompt
+ *     (Section III-A, causal);
+ *   - the score list Algorithm 1's bookkeeping accumulates over these rows: a_i = sum_t A_t[i],
+ *     n_i = n_tokens - i;
+ *   - while more than `budget` entries remain: Algorithm 1's selection and merge with these
+ *     (fixed) scores, protected entries as in wkv_step.
+ * For n_tokens <= budget + 1 the result is that of n_tokens calls of wkv_step; beyond that it
+ * is a different function (a streamed token attends to an already compressed cache).
+ *   q, k, v : DEVICE pointers, contiguous [n_tokens, batch, heads, head_dim] in the handle's
+ *             dtype, 16-byte aligned, read only.
+ *   out     : DEVICE pointer of the same shape, or NULL if the outputs are not wanted.
+ * Built for 16-bit caches with head_dim 64 or 128 and the average or cumulative scoring rule
+ * (WKV_ESIZE / WKV_EINVAL otherwise); 1 <= n_tokens <= WKV_MAX_PROMPT.  Allocates and frees its
+ * own device scratch (16 bytes per token and unit, plus a copy of v when values are merged)
+ * and returns when the work on `stream` has completed.  The eviction log is not written.
+ * On error the cache is unchanged, except for WKV_EHIP after the launch.
+ */
+int wkv_prefill(wkv_handle* h, const void* q, const void* k, const void* v, void* out,
+                int n_tokens, void* stream);
 
 /* what wkv_state reads back */
 #define WKV_STEP       0  /* int64[1]            tokens processed so far                             */

@@ -22,12 +22,13 @@ LIB_PATH = os.path.join(_HERE, "libwkv.so")
 WKV_FP32, WKV_FP16, WKV_BF16 = 0, 1, 2
 WKV_OK, WKV_EINVAL, WKV_ENOMEM, WKV_EHIP, WKV_ESIZE = 0, -1, -2, -3, -4
 WKV_MAX_BUDGET = 4095
+WKV_MAX_PROMPT = 8192
 WKV_SCORE_AVERAGE, WKV_SCORE_CUMULATIVE, WKV_SCORE_LAST = 0, 1, 2
 WKV_MERGE_CONVEX, WKV_MERGE_NONE = 0, 1
 (WKV_STEP, WKV_LEN, WKV_K, WKV_V, WKV_SCORE_SUM, WKV_COUNT, WKV_POS, WKV_NMERGED,
  WKV_EVICT_POS, WKV_EVICT_SLOT, WKV_STATUS) = range(11)
 
-EXPORTS = ("wkv_create", "wkv_create_ex", "wkv_step", "wkv_state", "wkv_load", "wkv_destroy",
+EXPORTS = ("wkv_create", "wkv_create_ex", "wkv_step", "wkv_prefill", "wkv_state", "wkv_load", "wkv_destroy",
            "wkv_last_error", "wkv_workspace_bytes", "wkv_step_bytes", "wkv_version")
 
 
@@ -51,6 +52,7 @@ _lib = C.CDLL(LIB_PATH)
 _lib.wkv_create.argtypes = [C.POINTER(C.c_void_p)] + [C.c_int] * 6
 _lib.wkv_create_ex.argtypes = [C.POINTER(C.c_void_p), C.POINTER(wkv_options)]
 _lib.wkv_step.argtypes = [C.c_void_p] * 6
+_lib.wkv_prefill.argtypes = [C.c_void_p] * 5 + [C.c_int, C.c_void_p]
 _lib.wkv_state.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.c_size_t]
 _lib.wkv_load.argtypes = [C.c_void_p, C.c_int64, C.c_int] + [C.c_void_p] * 4
 _lib.wkv_destroy.argtypes = [C.c_void_p]
@@ -97,6 +99,11 @@ def wkv_step(h, q: int, k_new: int, v_new: int, out: int, stream: int = 0) -> No
     _check(_lib.wkv_step(h, q, k_new, v_new, out, stream))
 
 
+def wkv_prefill(h, q: int, k: int, v: int, out: int, n_tokens: int, stream: int = 0) -> None:
+    """q, k, v, out: device addresses of [n_tokens, batch, heads, head_dim] arrays (out may be 0)."""
+    _check(_lib.wkv_prefill(h, q, k, v, out or None, n_tokens, stream))
+
+
 def wkv_state_raw(h, what: int, dst: np.ndarray) -> None:
     _check(_lib.wkv_state(h, what, dst.ctypes.data_as(C.c_void_p), dst.nbytes))
 
@@ -140,6 +147,15 @@ class Cache:
             import torch
             stream = torch.cuda.current_stream().cuda_stream
         wkv_step(self.h, q.data_ptr(), k_new.data_ptr(), v_new.data_ptr(), out.data_ptr(), stream)
+
+    def prefill(self, q, k, v, out=None, stream=None):
+        """q, k, v (and out, if wanted): torch tensors on the GPU, contiguous [n_tokens, batch, heads, head_dim]
+        (or [n_tokens, units, head_dim]); the cache must be empty."""
+        if stream is None:
+            import torch
+            stream = torch.cuda.current_stream().cuda_stream
+        wkv_prefill(self.h, q.data_ptr(), k.data_ptr(), v.data_ptr(), out.data_ptr() if out is not None else 0,
+                    q.shape[0], stream)
 
     def step_ptr(self, q, k_new, v_new, out, stream=0):
         wkv_step(self.h, q, k_new, v_new, out, stream)

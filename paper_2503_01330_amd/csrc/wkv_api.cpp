@@ -248,6 +248,57 @@ int wkv_step(wkv_handle* h, const void* q, const void* k_new, const void* v_new,
     return WKV_OK;
 }
 
+int wkv_prefill(wkv_handle* h, const void* q, const void* k, const void* v, void* out, int n_tokens,
+                void* stream)
+{
+    if (!h) return fail(WKV_EINVAL, "null handle");
+    if (!q || !k || !v) return fail(WKV_EINVAL, "null device pointer");
+    if ((((uintptr_t)q | (uintptr_t)k | (uintptr_t)v | (uintptr_t)out) & 15) != 0)
+        return fail(WKV_EINVAL, "q, k, v and out must be 16-byte aligned");
+    if (h->t != 0) return fail(WKV_EINVAL, "wkv_prefill needs an empty cache (%lld tokens processed)", (long long)h->t);
+    if (n_tokens < 1) return fail(WKV_EINVAL, "n_tokens must be positive");
+    if (n_tokens > WKV_MAX_PROMPT) return fail(WKV_ESIZE, "n_tokens %d exceeds WKV_MAX_PROMPT %d", n_tokens, WKV_MAX_PROMPT);
+    const wkv_options& o = h->opt;
+    if (o.dtype == WKV_FP32 || o.head_dim > 128)
+        return fail(WKV_ESIZE, "wkv_prefill is built for 16-bit caches with head_dim 64 or 128");
+    if (o.score_mode == WKV_SCORE_LAST)
+        return fail(WKV_EINVAL, "the last-step scoring rule is not defined for a prompt");
+    int dev;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return fail(WKV_EHIP, "hipGetDevice: %s", hipGetErrorString(e));
+    if (dev != h->device) return fail(WKV_EINVAL, "handle belongs to device %d, current device is %d", h->device, dev);
+    int lds_max = 0;
+    e = hipDeviceGetAttribute(&lds_max, hipDeviceAttributeMaxSharedMemoryPerBlock, h->device);
+    if (e == hipSuccess && wkv_prefill_lds_bytes(n_tokens) > (size_t)lds_max)
+        return fail(WKV_ESIZE, "a prompt of %d tokens needs %zu bytes of LDS, the device offers %d", n_tokens,
+                    wkv_prefill_lds_bytes(n_tokens), lds_max);
+
+    const size_t units = h->c.units, P = (size_t)n_tokens;
+    const size_t rowb = (size_t)o.head_dim * dtype_bytes(o.dtype);
+    const bool need_vw = o.merge_mode == WKV_MERGE_CONVEX && n_tokens > o.budget;
+    double *lse = nullptr, *a = nullptr;
+    void* vw = nullptr;
+    e = hipMalloc((void**)&lse, units * P * sizeof(double));
+    if (e == hipSuccess) e = hipMalloc((void**)&a, units * P * sizeof(double));
+    if (e == hipSuccess && need_vw) e = hipMalloc(&vw, units * P * rowb);
+    if (e != hipSuccess) {
+        (void)hipGetLastError();
+        if (lse) (void)hipFree(lse);
+        if (a) (void)hipFree(a);
+        return fail(e == hipErrorOutOfMemory ? WKV_ENOMEM : WKV_EHIP, "scratch for a prompt of %d tokens: %s",
+                    n_tokens, hipGetErrorString(e));
+    }
+    e = wkv_launch_prefill(h->c, o.dtype, o.head_dim, q, k, v, out, lse, a, vw, n_tokens, (hipStream_t)stream);
+    const hipError_t e2 = hipStreamSynchronize((hipStream_t)stream);
+    (void)hipFree(lse); (void)hipFree(a);
+    if (vw) (void)hipFree(vw);
+    if (e != hipSuccess) return fail(WKV_EHIP, "kernel launch: %s", hipGetErrorString(e));
+    if (e2 != hipSuccess) return fail(WKV_EHIP, "hipStreamSynchronize: %s", hipGetErrorString(e2));
+    h->t = n_tokens;
+    h->log_from = n_tokens;
+    return WKV_OK;
+}
+
 int wkv_state(wkv_handle* h, int what, void* dst, size_t bytes)
 {
     if (!h || !dst) return fail(WKV_EINVAL, "null argument");

@@ -1,0 +1,388 @@
+// Bulk prefill of an empty WeightedKV cache with a prompt of P tokens, gfx950.
+//
+// The paper streams tokens one by one (Algorithm 1) and gives no procedure for a prompt that
+// arrives at once.  What is computed here: row t of the prompt is softmax attention of q_t over
+// tokens 0..t of the UNcompressed prompt (Section III-A, scale of Section III-B); the score list
+// is what Algorithm 1's bookkeeping accumulates over these rows, a_i = sum_t A_t[i], with
+// n_i = P - i; then, while more than m entries remain, Algorithm 1's selection and merge are
+// repeated with these (now fixed) scores.  For P <= m + 1 this is exactly Algorithm 1 fed token
+// by token; beyond that it is a different function (streamed tokens attend to an already
+// compressed cache).
+//
+// Three kernels:
+//   1. wkv_prefill_rows: causal attention, one wave per tile of 16 queries, keys in tiles of 16.
+//      The logits are a dense contraction: v_mfma_f64_16x16x4_f64, fp16/bf16 inputs converted to
+//      fp64 (products and sums then reproduce an fp64 reference to ~1e-16, which is what makes
+//      the later selection reproduce it exactly, as in the decode kernels).  Online softmax in
+//      fp64; P.V in fp32 with v_mfma_f32_16x16x4_f32, fed straight from the registers the
+//      logits arrive in.  Writes o_t and the log-sum-exp of every row.
+//   2. wkv_prefill_scores: the column sums a_i = sum_{t >= i} exp(s_ti - lse_t): one wave per
+//      tile of 16 keys, looping over the query tiles below the diagonal, the same fp64 MFMA
+//      contraction again (recomputing the logits costs less than storing P^2/2 of them);
+//      sums stay in registers, no atomics, fixed order.
+//   3. wkv_prefill_compress: one workgroup per unit: rank of every candidate by (score, token),
+//      the P - m lowest are removed; survivors are laid out in token order in the cache; every
+//      run of removed tokens is folded into the survivor on its right in ascending score order,
+//      exactly the sequence of merges the repeated selection would perform.
+//
+// MFMA operand layouts (one wave; g = lane / 16, x = lane % 16), as measured on gfx950:
+//   both: A operand = A[row x][k = g], B operand = B[k = g][column x];
+//   f64 16x16x4: result register r holds D[row g + 4r][column x];
+//   f32 16x16x4: result register r holds D[row 4g + r][column x].
+// The reduction index of a contraction may be permuted at will as long as A and B agree, so a lane
+// simply takes a contiguous quarter of its row: MFMA step kk uses element g*(D/4) + kk of both.
+#include "wkv_internal.h"
+#include "wkv_device.h"
+
+namespace {
+
+typedef double double4_t __attribute__((ext_vector_type(4)));
+typedef float  float4_t  __attribute__((ext_vector_type(4)));
+
+constexpr int TILE = 16;
+
+// element e of a row fragment held as raw 32-bit words (two 16-bit elements per word)
+template <class TT> __device__ __forceinline__ float frag_elem(const uint32_t* w, int e) {
+    const uint32_t x = w[e >> 1];
+    if constexpr (__is_same(TT, TF16)) {
+        const half2_t h = __builtin_bit_cast(half2_t, x);
+        return (e & 1) ? (float)h.y : (float)h.x;
+    } else {
+        return __builtin_bit_cast(float, (e & 1) ? (x & 0xFFFF0000u) : (x << 16));
+    }
+}
+
+__device__ __forceinline__ double xor_max(double v, int mask) { return fmax(v, __shfl_xor(v, mask)); }
+
+// S^T tile: rows = 16 keys, columns = 16 queries; register r of lane (g, x) = key g + 4r, query x.
+template <class TT, int D>
+__device__ __forceinline__ double4_t logits_tile(const uint32_t (&kfrag)[D / 8], const double (&qd)[D / 4]) {
+    double4_t s = {0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+    for (int kk = 0; kk < D / 4; ++kk)
+        s = __builtin_amdgcn_mfma_f64_16x16x4f64((double)frag_elem<TT>(kfrag, kk), qd[kk], s, 0, 0, 0);
+    return s;
+}
+
+// ------------------------------------------------------------------ 1. rows
+// q, k, v, out: [P][units][D] (token-major, as a decode step sees them one token at a time).
+// lse: [units][P].  One workgroup = 4 waves = 4 consecutive query tiles of one unit.
+template <class TT, int D>
+__global__ __launch_bounds__(256)
+void wkv_prefill_rows(const void* __restrict__ q_, const void* __restrict__ k_, const void* __restrict__ v_,
+                      void* __restrict__ out_, double* __restrict__ lse, int P, int units)
+{
+    constexpr int CH = D / 4;                 // elements of a row per lane group
+    constexpr int ROWB = D * TT::BYTES;
+    const int lane = threadIdx.x & 63, wid = threadIdx.x >> 6;
+    const int g = lane >> 4, x = lane & 15;
+    const int ntiles = (P + TILE - 1) / TILE;
+    const int groups = (ntiles + 3) / 4;
+    const int u = blockIdx.x / groups;
+    const int qt = (groups - 1 - (int)(blockIdx.x % groups)) * 4 + wid;   // long rows are scheduled first
+    if (qt >= ntiles) return;
+    const size_t tok = (size_t)units * ROWB;                              // bytes from one token to the next
+    const char* qb = reinterpret_cast<const char*>(q_) + (size_t)u * ROWB;
+    const char* kb = reinterpret_cast<const char*>(k_) + (size_t)u * ROWB;
+    const char* vb = reinterpret_cast<const char*>(v_) + (size_t)u * ROWB;
+
+    // the query fragment: row 16 qt + x (clamped), elements g*CH .. g*CH+CH-1, scaled, fp64
+    double qd[CH];
+    {
+        const int tq = min(qt * TILE + x, P - 1);
+        uint32_t w[CH / 2];
+        load_words<CH / 2>(qb + (size_t)tq * tok + g * CH * TT::BYTES, w);
+        const double scale = 1.0 / sqrt((double)D);
+#pragma unroll
+        for (int e = 0; e < CH; ++e) qd[e] = (double)frag_elem<TT>(w, e) * scale;
+    }
+    double mrow = -INFINITY, lrow = 0.0;      // running maximum and sum of query x (same in the 4 lanes x, x+16, ...)
+    constexpr int NE = D / 16;                // output column sets: lane (g, x) owns columns NE*x .. NE*x+NE-1
+    float4_t o[NE];
+#pragma unroll
+    for (int e = 0; e < NE; ++e) o[e] = float4_t{0.f, 0.f, 0.f, 0.f};
+
+    for (int kt = 0; kt <= qt; ++kt) {
+        // K fragment: key 16 kt + x, the same quarter of the row as the query fragment
+        uint32_t kfrag[CH / 2];
+        load_words<CH / 2>(kb + (size_t)min(kt * TILE + x, P - 1) * tok + g * CH * TT::BYTES, kfrag);
+        // V fragments: keys 16 kt + g + 4r, columns NE*x .. NE*x+NE-1
+        uint32_t vfrag[4][NE / 2];
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+            load_words<NE / 2>(vb + (size_t)min(kt * TILE + g + 4 * r, P - 1) * tok + x * NE * TT::BYTES, vfrag[r]);
+
+        double4_t s = logits_tile<TT, D>(kfrag, qd);
+        if (kt == qt) {                       // the diagonal tile: key g + 4r may be attended by query x only if <= x
+#pragma unroll
+            for (int r = 0; r < 4; ++r) if (g + 4 * r > x) s[r] = -INFINITY;
+        }
+        double tmax = fmax(fmax(s[0], s[1]), fmax(s[2], s[3]));
+        tmax = xor_max(xor_max(tmax, 16), 32);
+        const double mnew = fmax(mrow, tmax);                 // finite: key 16 kt + 0 <= every query of a later tile,
+                                                              // and on the diagonal key x is attended by query x
+        const double resc = exp(mrow - mnew);                 // 0 on the first tile (mrow = -inf)
+        float p[4];
+        double psum = 0.0;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) { const double e = exp(s[r] - mnew); psum += e; p[r] = (float)e; }
+        psum += __shfl_xor(psum, 16);
+        psum += __shfl_xor(psum, 32);
+        lrow = lrow * resc + psum;
+        mrow = mnew;
+        // rescale the output rows this lane holds (queries 4g + r') by their own factor
+        const float rf = (float)resc;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const float f = __shfl(rf, 4 * g + r);
+#pragma unroll
+            for (int e = 0; e < NE; ++e) o[e][r] *= f;
+        }
+        // O[query][column] += sum over keys P[query][key] V[key][column]: A = P (k index = g: key g + 4r
+        // in step r), B = V[key g + 4r][column NE*x + e]
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+#pragma unroll
+            for (int e = 0; e < NE; ++e)
+                o[e] = __builtin_amdgcn_mfma_f32_16x16x4f32(p[r], frag_elem<TT>(vfrag[r], e), o[e], 0, 0, 0);
+    }
+
+    // o_t = O / l, log-sum-exp = m + log l
+    const float linv = (float)(1.0 / lrow);
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        const int t = qt * TILE + 4 * g + r;
+        const float f = __shfl(linv, 4 * g + r);
+        if (t < P && out_ != nullptr) {
+            char* dst = reinterpret_cast<char*>(out_) + (size_t)t * tok + (size_t)u * ROWB + x * NE * TT::BYTES;
+#pragma unroll
+            for (int e = 0; e < NE; ++e) store_elem<TT>(dst, e, o[e][r] * f);
+        }
+    }
+    if (g == 0 && qt * TILE + x < P) lse[(size_t)u * P + qt * TILE + x] = mrow + log(lrow);
+}
+
+// ------------------------------------------------------------------ 2. scores
+// a[u][i] = sum over rows t >= i of exp(s_ti - lse_t).  One wave per key tile.
+template <class TT, int D>
+__global__ __launch_bounds__(256)
+void wkv_prefill_scores(const void* __restrict__ q_, const void* __restrict__ k_, const double* __restrict__ lse,
+                        double* __restrict__ a, int P, int units)
+{
+    constexpr int CH = D / 4;
+    constexpr int ROWB = D * TT::BYTES;
+    const int lane = threadIdx.x & 63, wid = threadIdx.x >> 6;
+    const int g = lane >> 4, x = lane & 15;
+    const int ntiles = (P + TILE - 1) / TILE;
+    const int groups = (ntiles + 3) / 4;
+    const int u = blockIdx.x / groups;
+    const int kt = (int)(blockIdx.x % groups) * 4 + wid;                  // low key tiles have the most rows: first
+    if (kt >= ntiles) return;
+    const size_t tok = (size_t)units * ROWB;
+    const char* qb = reinterpret_cast<const char*>(q_) + (size_t)u * ROWB;
+    const char* kb = reinterpret_cast<const char*>(k_) + (size_t)u * ROWB;
+    const double scale = 1.0 / sqrt((double)D);
+
+    uint32_t kfrag[CH / 2];
+    load_words<CH / 2>(kb + (size_t)min(kt * TILE + x, P - 1) * tok + g * CH * TT::BYTES, kfrag);
+    double acc[4] = {0.0, 0.0, 0.0, 0.0};
+    for (int qt = kt; qt < ntiles; ++qt) {
+        const int tq = qt * TILE + x;
+        const int tqc = min(tq, P - 1);
+        uint32_t w[CH / 2];
+        load_words<CH / 2>(qb + (size_t)tqc * tok + g * CH * TT::BYTES, w);
+        const double l = lse[(size_t)u * P + tqc];
+        double qd[CH];
+#pragma unroll
+        for (int e = 0; e < CH; ++e) qd[e] = (double)frag_elem<TT>(w, e) * scale;
+        const double4_t s = logits_tile<TT, D>(kfrag, qd);
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int key = kt * TILE + g + 4 * r;
+            const bool on = tq < P && key <= tq;                           // causal, and inside the prompt
+            acc[r] += on ? exp(s[r] - l) : 0.0;
+        }
+    }
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        const double c = row_allsum(acc[r]);                               // over the 16 queries x
+        const int key = kt * TILE + g + 4 * r;
+        if (x == 0 && key < P) a[(size_t)u * P + key] = c;
+    }
+}
+
+// ------------------------------------------------------------------ 3. compress
+// One workgroup per unit.  sc[] (LDS, fp64) holds the score of every token; fl[] one byte per
+// token: 1 = removed.  Afterwards the same LDS holds, as int32, the right neighbour links.
+template <class TT, int D>
+__global__ __launch_bounds__(1024)
+void wkv_prefill_compress(WkvCache c, const void* __restrict__ k_, const void* __restrict__ v_,
+                          void* __restrict__ vw_, const double* __restrict__ a, int P)
+{
+    constexpr int ROWB = D * TT::BYTES;
+    constexpr int EPW = (D + 63) / 64;
+    const int tid = threadIdx.x, NT = blockDim.x, lane = tid & 63, wid = tid >> 6, NW = NT >> 6;
+    const int u = blockIdx.x, m = c.m;
+    const size_t tok = (size_t)c.units * ROWB;
+    const char* kb = reinterpret_cast<const char*>(k_) + (size_t)u * ROWB;
+    const char* vb = reinterpret_cast<const char*>(v_) + (size_t)u * ROWB;
+    char* Kc = reinterpret_cast<char*>(c.K) + (size_t)u * m * ROWB;
+    char* Vc = reinterpret_cast<char*>(c.V) + (size_t)u * m * ROWB;
+    double*  au = c.a + (size_t)u * m;
+    int32_t* pu = c.pos + (size_t)u * m;
+    int32_t* nu = c.nxt + (size_t)u * m;
+    const double* ap = a + (size_t)u * P;
+
+    extern __shared__ double lds[];
+    double*  sc = lds;                                        // [P]
+    int32_t* slot = reinterpret_cast<int32_t*>(sc + P);       // [P] slot of a survivor, -1 for a removed token
+    int32_t* wcnt = slot + P;                                 // [NT] scan scratch
+    const int L = (P < m) ? P : m;
+    const int nrem = P - L;                                   // tokens to remove
+    const int lo = c.n_sink, hi = P - c.R;                    // candidates: lo <= token < hi
+
+    for (int i = tid; i < P; i += NT) {
+        const double ai = ap[i];
+        double s = (c.score_mode == 0) ? ai / (double)(P - i) : ai;       // abar = a / n, n_i = P - i
+        if (!(s == s) || s == INFINITY) { s = INFINITY; atomicAdd(&c.status[1], 1); }
+        sc[i] = s;
+    }
+    __syncthreads();
+    // rank among the candidates by (score, token); the nrem lowest are removed
+    for (int i = tid; i < P; i += NT) {
+        int removed = 0;
+        if (nrem > 0 && i >= lo && i < hi) {
+            const double si = sc[i];
+            int rank = 0;
+            for (int k = lo; k < hi; ++k) {
+                const double sk = sc[k];
+                rank += (sk < si || (sk == si && k < i)) ? 1 : 0;
+            }
+            removed = rank < nrem;
+        }
+        slot[i] = removed ? -1 : 0;
+    }
+    __syncthreads();
+    // survivors get consecutive slots in token order: exclusive scan over the keep flags
+    const int per = (P + NT - 1) / NT;
+    const int b0 = min(tid * per, P), b1 = min(b0 + per, P);
+    int mine = 0;
+    for (int i = b0; i < b1; ++i) mine += (slot[i] == 0) ? 1 : 0;
+    wcnt[tid] = mine;
+    __syncthreads();
+    if (tid == 0) { int run = 0; for (int w = 0; w < NT; ++w) { const int t = wcnt[w]; wcnt[w] = run; run += t; } }
+    __syncthreads();
+    {
+        int sidx = wcnt[tid];
+        for (int i = b0; i < b1; ++i) if (slot[i] == 0) slot[i] = sidx++;
+    }
+    __syncthreads();
+    // score sums, token indices, links and keys of the survivors
+    for (int i = tid; i < P; i += NT) {
+        const int sidx = slot[i];
+        if (sidx >= 0) { au[sidx] = ap[i]; pu[sidx] = i; nu[sidx] = (sidx + 1 < L) ? sidx + 1 : -1; }
+    }
+    for (int i = wid; i < P; i += NW) {                       // one wave per row
+        const int sidx = slot[i];
+        if (sidx < 0) continue;
+#pragma unroll
+        for (int e = 0; e < EPW; ++e) {
+            const int col = lane + 64 * e;
+            if (col < D) store_bits<TT>(Kc + (size_t)sidx * ROWB, col, load_bits<TT>(kb + (size_t)i * tok, col));
+        }
+    }
+    // values.  A survivor at token i with previous survivor at token i0 receives the removed tokens
+    // i0+1 .. i-1, one after the other in ascending (score, token) order; each folds into whatever is
+    // then its right neighbour (a still present token of the run, or the survivor).  One wave per
+    // run; vw_ is a working copy of V ([units][P][D]) whose rows are rewritten in place.
+    char* vw = reinterpret_cast<char*>(vw_) + (size_t)u * P * ROWB;
+    const bool merging = c.merge_mode == 0;
+    __syncthreads();
+    for (int i = wid; i < P; i += NW) {
+        const int sidx = slot[i];
+        if (sidx < 0) continue;
+        int i0 = i - 1;
+        while (i0 >= 0 && slot[i0] < 0) --i0;                  // previous survivor (or -1)
+        const int len = i - 1 - i0;                            // removed tokens i0+1 .. i-1
+        if (merging && len > 0) {
+            // process the run in ascending (score, token): repeated arg-min over what is left;
+            // a processed token is marked in slot[] with -2 (only this wave touches the run)
+            for (int step = 0; step < len; ++step) {
+                Best b = { INFINITY, NONE_POS, -1 };
+                for (int j = i0 + 1 + lane; j < i; j += 64)
+                    if (slot[j] == -1 && better(sc[j], j, b)) b = { sc[j], j, j };
+                b = wave_argmin(b);
+                const int j = b.phys;
+                if (j < 0) break;                              // cannot happen: len tokens are pending
+                int r = j + 1;
+                while (slot[r] == -2) ++r;                     // right neighbour still present (r <= i)
+                const double sj = sc[j], sr = sc[r];
+                const double den = sj + sr;
+                const bool zero_den = !(den > 0.0);
+#pragma unroll
+                for (int e = 0; e < EPW; ++e) {
+                    const int col = lane + 64 * e;
+                    if (col < D) {
+                        const double vj = (double)load_elem<TT>(vw + (size_t)j * ROWB, col);
+                        const double vr = (double)load_elem<TT>(vw + (size_t)r * ROWB, col);
+                        const double y = zero_den ? 0.5 * vj + 0.5 * vr : (sj * vj + sr * vr) / den;
+                        store_elem_f64<TT>(vw + (size_t)r * ROWB, col, y);
+                    }
+                }
+                if (lane == 0 && zero_den) atomicAdd(&c.status[0], 1);
+                if (lane == 0) slot[j] = -2;
+                __builtin_amdgcn_s_waitcnt(0);                 // the row just written is read again by a later merge
+            }
+        }
+        const char* src = (merging && P > m) ? vw + (size_t)i * ROWB : vb + (size_t)i * tok;
+#pragma unroll
+        for (int e = 0; e < EPW; ++e) {
+            const int col = lane + 64 * e;
+            if (col < D) store_bits<TT>(Vc + (size_t)sidx * ROWB, col, load_bits<TT>(src, col));
+        }
+    }
+}
+
+// copies v [P][units][D] into the working layout [units][P][D]
+template <int ROWB>
+__global__ void wkv_prefill_copy_v(const void* __restrict__ v_, void* __restrict__ vw_, int P, int units)
+{
+    const size_t n16 = (size_t)P * units * (ROWB / 16);
+    for (size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x; idx < n16; idx += (size_t)gridDim.x * blockDim.x) {
+        const size_t part = idx % (ROWB / 16), row = idx / (ROWB / 16);
+        const size_t t = row / units, u = row % units;
+        reinterpret_cast<uint4*>(vw_)[(u * P + t) * (ROWB / 16) + part] = reinterpret_cast<const uint4*>(v_)[idx];
+    }
+}
+
+template <class TT, int D>
+hipError_t run(const WkvCache& c, const void* q, const void* k, const void* v, void* out,
+               double* lse, double* a, void* vw, int P, hipStream_t stream)
+{
+    const int ntiles = (P + TILE - 1) / TILE, groups = (ntiles + 3) / 4;
+    hipLaunchKernelGGL((wkv_prefill_rows<TT, D>), dim3(c.units * groups), dim3(256), 0, stream, q, k, v, out, lse, P, c.units);
+    hipLaunchKernelGGL((wkv_prefill_scores<TT, D>), dim3(c.units * groups), dim3(256), 0, stream, q, k, lse, a, P, c.units);
+    if (c.merge_mode == 0 && P > c.m)
+        hipLaunchKernelGGL((wkv_prefill_copy_v<D * TT::BYTES>), dim3(2048), dim3(256), 0, stream, v, vw, P, c.units);
+    const size_t lds = wkv_prefill_lds_bytes(P);
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&wkv_prefill_compress<TT, D>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL((wkv_prefill_compress<TT, D>), dim3(c.units), dim3(1024), lds, stream, c, k, v, vw, a, P);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+size_t wkv_prefill_lds_bytes(int P) { return (size_t)P * 12 + 1024 * 4; }
+
+hipError_t wkv_launch_prefill(const WkvCache& c, int dtype, int head_dim, const void* q, const void* k,
+                              const void* v, void* out, double* lse, double* a, void* vw, int P,
+                              hipStream_t stream)
+{
+    if (dtype == 1 && head_dim == 64)  return run<TF16, 64>(c, q, k, v, out, lse, a, vw, P, stream);
+    if (dtype == 1 && head_dim == 128) return run<TF16, 128>(c, q, k, v, out, lse, a, vw, P, stream);
+    if (dtype == 2 && head_dim == 64)  return run<TBF16, 64>(c, q, k, v, out, lse, a, vw, P, stream);
+    if (dtype == 2 && head_dim == 128) return run<TBF16, 128>(c, q, k, v, out, lse, a, vw, P, stream);
+    return hipErrorInvalidValue;
+}

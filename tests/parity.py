@@ -111,6 +111,77 @@ def exact_fraction(got, ref, dtype):
     return float((got == r).mean())
 
 
+def check_cache_state(cache, orc, sel, cfg, T):
+    """The library's cache against the oracle's, unit by unit: token positions, counts, merge counts
+    and keys bit-exact, score sums to 1e-9, values within the output tolerance.  Returns the number
+    of units whose values are bit-identical."""
+    assert cache.tokens == T and cache.length == min(T, cfg.budget)
+    K = cache.state(wkv.WKV_K)[sel]; V = cache.state(wkv.WKV_V)[sel]
+    a = cache.state(wkv.WKV_SCORE_SUM)[sel]; n = cache.state(wkv.WKV_COUNT)[sel]
+    pos = cache.state(wkv.WKV_POS)[sel]; nm = cache.state(wkv.WKV_NMERGED)[sel]
+    Kf = synth.storage_to_f32(K, cfg.dtype).astype(np.float64)
+    Vf = synth.storage_to_f32(V, cfg.dtype).astype(np.float64)
+    v_exact = 0
+    for i in range(len(sel)):
+        st = orc.state(i)
+        assert np.array_equal(pos[i], st["pos"]), f"retained token positions differ (unit {sel[i]})"
+        assert np.array_equal(n[i], st["n"]), "counts differ"
+        assert np.array_equal(nm[i], st["nmerged"]), "merge counts differ"
+        assert np.array_equal(Kf[i], st["K"]), "retained keys differ"
+        assert np.allclose(a[i], st["a"], rtol=1e-9, atol=0), "score sums differ"
+        check_outputs(Vf[i], st["V"], cfg.dtype, what="merged values")
+        v_exact += int(np.array_equal(Vf[i], st["V"]))
+    status = cache.state(wkv.WKV_STATUS)
+    assert status[1] == 0, "non-finite scores flagged"
+    return v_exact
+
+
+def gpu_prefill(cfg, P, layer=0, units_sel=None, want_out=True, **create_kw):
+    """Prefill a fresh handle with the first P tokens of the stream.  Returns dict(out [P,U',d] f64,
+    cache, inputs of the selected units as exact fp32, the device tensors of the whole stream)."""
+    st = synth.Stream(cfg, layer)
+    q, k, v = st.steps(0, cfg.steps)
+    create_kw.setdefault("split", 1)
+    cache = wkv.Cache(cfg.batch, cfg.heads, cfg.head_dim, cfg.budget, cfg.recent,
+                      synth.DTYPE_CODE[cfg.dtype], **create_kw)
+    sel = np.arange(cfg.units) if units_sel is None else np.asarray(units_sel)
+    tq, tk, tv = (to_device(x, cfg.dtype) for x in (q, k, v))
+    out = torch.zeros_like(tq) if want_out else None
+    cache.prefill(tq[:P], tk[:P], tv[:P], None if out is None else out[:P])
+    torch.cuda.synchronize()
+    f32 = lambda x: synth.storage_to_f32(x[:, sel], cfg.dtype)
+    return dict(out=None if out is None else out_to_f64(out[:P][:, torch.from_numpy(sel).cuda()], cfg.dtype),
+                cache=cache, q=f32(q), k=f32(k), v=f32(v), sel=sel, dev=(tq, tk, tv, out), P=P)
+
+
+def compare_prefill(cfg, g, decode_steps=0, **orc_kw):
+    """gpu_prefill result against the oracle's prefill, then `decode_steps` streamed tokens on both."""
+    P, sel = g["P"], g["sel"]
+    orc = oracle.Oracle(len(sel), cfg.head_dim, cfg.budget, cfg.recent, storage=cfg.dtype, **orc_kw)
+    ref = orc.prefill(g["q"][:P], g["k"][:P], g["v"][:P])
+    stats = {}
+    if g["out"] is not None:
+        stats["out_err"] = check_outputs(g["out"], ref["out"], cfg.dtype)
+        stats["out_exact"] = exact_fraction(g["out"], ref["out"], cfg.dtype)
+    stats["v_bit_exact_units"] = check_cache_state(g["cache"], orc, sel, cfg, P)
+    if ref["evict_score"].size:
+        gaps = np.diff(ref["evict_score"], axis=0) / ref["evict_score"][1:]
+        stats["min_gap"] = float(gaps.min()) if gaps.size else float("nan")
+    if decode_steps:
+        tq, tk, tv, out = g["dev"]
+        cache = g["cache"]
+        for t in range(P, P + decode_steps):
+            cache.step(tq[t], tk[t], tv[t], out[t])
+        torch.cuda.synchronize()
+        gp, _ = cache.evictions(decode_steps)
+        r2 = orc.run(g["q"][P:P + decode_steps], g["k"][P:P + decode_steps], g["v"][P:P + decode_steps])
+        assert np.array_equal(gp[:, sel], r2["evict_pos"]), "evictions after the prefill differ"
+        got = out_to_f64(out[P:P + decode_steps][:, torch.from_numpy(sel).cuda()], cfg.dtype)
+        check_outputs(got, r2["out"], cfg.dtype)
+        check_cache_state(cache, orc, sel, cfg, P + decode_steps)
+    return stats
+
+
 def compare(cfg, g, check_state=True, log=print, **orc_kw):
     """Full comparison of a gpu_stream result with the oracle on the same inputs."""
     sel = g["sel"]
@@ -134,25 +205,6 @@ def compare(cfg, g, check_state=True, log=print, **orc_kw):
                  min_gap=float(np.nanmin((ref["runner_up"] - ref["evict_score"]) / ref["evict_score"]))
                  if np.isfinite(ref["evict_score"]).any() else float("nan"))
     if check_state:
-        cache = g["cache"]
         T = g["out"].shape[0]
-        assert cache.tokens == T and cache.length == min(T, cfg.budget)
-        K = cache.state(wkv.WKV_K)[sel]; V = cache.state(wkv.WKV_V)[sel]
-        a = cache.state(wkv.WKV_SCORE_SUM)[sel]; n = cache.state(wkv.WKV_COUNT)[sel]
-        pos = cache.state(wkv.WKV_POS)[sel]; nm = cache.state(wkv.WKV_NMERGED)[sel]
-        Kf = synth.storage_to_f32(K, cfg.dtype).astype(np.float64)
-        Vf = synth.storage_to_f32(V, cfg.dtype).astype(np.float64)
-        v_exact = 0
-        for i in range(len(sel)):
-            st = ref["orc"].state(i)
-            assert np.array_equal(pos[i], st["pos"]), "retained token positions differ"
-            assert np.array_equal(n[i], st["n"]), "counts differ"
-            assert np.array_equal(nm[i], st["nmerged"]), "merge counts differ"
-            assert np.array_equal(Kf[i], st["K"]), "retained keys differ"
-            assert np.allclose(a[i], st["a"], rtol=1e-9, atol=0), "score sums differ"
-            check_outputs(Vf[i], st["V"], cfg.dtype, what="merged values")
-            v_exact += int(np.array_equal(Vf[i], st["V"]))
-        stats["v_bit_exact_units"] = v_exact
-        status = cache.state(wkv.WKV_STATUS)
-        assert status[1] == 0, "non-finite scores flagged"
+        stats["v_bit_exact_units"] = check_cache_state(g["cache"], ref["orc"], sel, cfg, T)
     return stats

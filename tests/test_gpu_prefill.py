@@ -1,0 +1,121 @@
+"""GPU parity of the bulk prefill (wkv_prefill) against the oracle's prefill: outputs of every
+prompt row, the compressed cache (token positions, counts, merge counts, keys bit-exact; score
+sums to 1e-9; merged values within the output tolerance), and decode steps that follow."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2503_01330_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+if torch.cuda.is_available():
+    import parity
+    from paper_2503_01330_amd import binding as wkv
+
+
+def _run(cfg, P, decode_steps=0, units_sel=None, **kw):
+    g = parity.gpu_prefill(cfg, P, units_sel=units_sel, **kw)
+    try:
+        okw = {k: kw[k] for k in ("n_sink", "score_mode", "merge_mode") if k in kw}
+        stats = parity.compare_prefill(cfg, g, decode_steps=decode_steps, **okw)
+    finally:
+        g["cache"].close()
+    print(f"\n  {cfg.name} P={P}: {stats}", flush=True)
+    return stats
+
+
+@pytest.mark.parametrize("dtype", ["fp16", "bf16"])
+@pytest.mark.parametrize("d", [64, 128])
+def test_prompt_lengths_around_the_tile_and_the_budget(dtype, d):
+    """1 token, ragged tiles (15, 17, 100), prompt = budget, budget + 1 (where the prefill must equal
+    token-by-token streaming), and several times the budget."""
+    for P, m, R in ((1, 8, 1), (15, 20, 3), (17, 16, 2), (100, 100, 9), (101, 100, 9), (100, 37, 5), (333, 40, 1)):
+        cfg = synth.StreamConfig(f"pre{P}", 8000 + P, 2, 3, d, dtype, P + 12, m, R)
+        _run(cfg, P, decode_steps=12)
+
+
+def test_prefill_equals_streaming_on_the_gpu_up_to_budget_plus_one():
+    """The same property as the oracle's pin, on the library: a prompt of m + 1 tokens through
+    wkv_prefill and through m + 1 calls of wkv_step gives the same cache."""
+    cfg = synth.StreamConfig("pre-eq", 8100, 1, 4, 128, "fp16", 65, 64, 4)
+    a = parity.gpu_prefill(cfg, 65)
+    b = parity.gpu_stream(cfg)
+    try:
+        for what in (wkv.WKV_POS, wkv.WKV_COUNT, wkv.WKV_NMERGED, wkv.WKV_K, wkv.WKV_V):
+            assert np.array_equal(a["cache"].state(what), b["cache"].state(what)), what
+        np.testing.assert_allclose(a["cache"].state(wkv.WKV_SCORE_SUM), b["cache"].state(wkv.WKV_SCORE_SUM), rtol=1e-12)
+        parity.check_outputs(a["out"], b["out"], cfg.dtype)
+    finally:
+        a["cache"].close(); b["cache"].close()
+
+
+def test_sinks_eviction_only_and_cumulative_scores():
+    cfg = synth.StreamConfig("pre-var", 8200, 1, 5, 128, "fp16", 300, 48, 8)
+    _run(cfg, 280, decode_steps=20, n_sink=4)
+    _run(cfg, 280, decode_steps=20, merge_mode=wkv.WKV_MERGE_NONE)
+    _run(cfg, 280, decode_steps=20, merge_mode=wkv.WKV_MERGE_NONE, score_mode=wkv.WKV_SCORE_CUMULATIVE)
+
+
+def test_long_runs_of_removed_tokens():
+    """A tiny budget under a long prompt: almost everything is removed, runs of hundreds of tokens fold
+    into one survivor in score order."""
+    cfg = synth.StreamConfig("pre-runs", 8300, 1, 3, 64, "bf16", 1210, 6, 2)
+    _run(cfg, 1200, decode_steps=10)
+
+
+def test_prefill_then_sliced_decode():
+    cfg = synth.StreamConfig("pre-split", 8400, 1, 2, 128, "fp16", 700, 300, 16)
+    _run(cfg, 650, decode_steps=50, split=4)
+
+
+def test_outputs_may_be_skipped():
+    cfg = synth.StreamConfig("pre-noout", 8500, 1, 2, 128, "fp16", 200, 50, 4)
+    g = parity.gpu_prefill(cfg, 200, want_out=False)
+    try:
+        parity.compare_prefill(cfg, g)
+    finally:
+        g["cache"].close()
+
+
+def test_argument_checks():
+    code = synth.DTYPE_CODE
+    x = torch.zeros(64, 2, 128, dtype=torch.float16, device="cuda")
+    c = wkv.Cache(1, 2, 128, 16, 2, code["fp16"])
+    try:
+        with pytest.raises(wkv.WkvError) as e:
+            wkv.wkv_prefill(c.h, x.data_ptr(), x.data_ptr(), x.data_ptr(), 0, 0)
+        assert e.value.code == wkv.WKV_EINVAL
+        with pytest.raises(wkv.WkvError) as e:
+            wkv.wkv_prefill(c.h, x.data_ptr(), x.data_ptr(), x.data_ptr(), 0, wkv.WKV_MAX_PROMPT + 1)
+        assert e.value.code == wkv.WKV_ESIZE
+        with pytest.raises(wkv.WkvError) as e:
+            wkv.wkv_prefill(c.h, x.data_ptr() + 2, x.data_ptr(), x.data_ptr(), 0, 8)
+        assert e.value.code == wkv.WKV_EINVAL
+        assert c.tokens == 0
+        c.prefill(x, x, x)
+        assert c.tokens == 64 and c.length == 16
+        with pytest.raises(wkv.WkvError) as e:       # not empty any more
+            c.prefill(x, x, x)
+        assert e.value.code == wkv.WKV_EINVAL
+    finally:
+        c.close()
+    for kw, dt, d in ((dict(), "fp32", 128), (dict(), "fp16", 256),
+                      (dict(score_mode=wkv.WKV_SCORE_LAST, merge_mode=wkv.WKV_MERGE_NONE), "fp16", 128)):
+        c = wkv.Cache(1, 2, d, 16, 2, code[dt], **kw)
+        try:
+            y = torch.zeros(8, 2, d, dtype={"fp32": torch.float32, "fp16": torch.float16}[dt], device="cuda")
+            with pytest.raises(wkv.WkvError):
+                c.prefill(y, y, y)
+            assert c.tokens == 0
+        finally:
+            c.close()
+
+
+def test_llama_shaped_prompt_sampled_units():
+    """A 4096-token prompt into the stacked configuration's cache (batch 8 x 32 heads x 128 fp16,
+    budget 410), every unit on the GPU, 3 sampled units through the oracle, then 64 decode steps."""
+    cfg = synth.scaled(synth.CONFIGS["cfg3"], steps=4096 + 64, layers=1)
+    sel = np.sort(np.random.default_rng(11).choice(cfg.units, 3, replace=False))
+    stats = _run(cfg, 4096, decode_steps=64, units_sel=sel)
+    assert stats["min_gap"] >= 0
