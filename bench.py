@@ -28,6 +28,8 @@ def parse():
     ap.add_argument("--layers", type=int, default=0, help="override the number of stacked layers")
     ap.add_argument("--threads", type=int, default=0, help="workgroup size override (256/512/1024)")
     ap.add_argument("--split", type=int, default=0, help="workgroups per unit override (1/2/4/8/16; 0 = library's choice)")
+    ap.add_argument("--prefill-tokens", type=int, default=4096,
+                    help="prompt length of the bulk-prefill leg reported under 'prefill' (0 = skip it)")
     ap.add_argument("--skip-cpu-baseline", action="store_true")
     ap.add_argument("--also", default="cfg5", choices=["", "cfg2", "cfg4", "cfg5"],
                     help="second workload measured in the same run and reported under 'also' ('' = none)")
@@ -175,6 +177,44 @@ def main():
         result["also"] = {"config": {"workload": describe(e, args.also)}, "value": round(e["tokens_per_s"], 1),
                           "unit": "tokens/s", "ms_per_step": round(e["wall"] * 1e3 / K, 4),
                           "roofline": roofline(e, args.also)}
+
+    if args.prefill_tokens and cfg.dtype != "fp32" and cfg.head_dim <= 128:
+        # bulk prefill of one layer's empty cache with a prompt (not part of `value`): the prompt rows attend
+        # causally over the uncompressed prompt, then the cache is compressed to its budget
+        P = min(args.prefill_tokens, wkv.WKV_MAX_PROMPT)
+        pcfg = synth.scaled(cfg, steps=P)
+        q, k, v = synth.Stream(pcfg, 0).steps(0, P)
+        tq, tk, tv = (torch.from_numpy(x).to(dev) for x in (q, k, v))
+        out = torch.empty_like(tq)
+        code = synth.DTYPE_CODE[cfg.dtype]
+        stream = torch.cuda.current_stream().cuda_stream
+        times = []
+        for rep_i in range(3):
+            c = wkv.Cache(cfg.batch, cfg.heads, cfg.head_dim, cfg.budget, cfg.recent, code)
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            wkv.wkv_prefill(c.h, tq.data_ptr(), tk.data_ptr(), tv.data_ptr(), out.data_ptr(), P, stream)
+            e1.record()
+            torch.cuda.synchronize()
+            times.append(e0.elapsed_time(e1))
+            c.close()
+        ms = min(times[1:])
+        # the method's contractions: q.K^T once and P.V once over the causal half, 2 flops per multiply-add
+        flops = 2.0 * cfg.units * P * (P + 1) * cfg.head_dim
+        result["prefill"] = {
+            "config": {"workload": f"{args.workload}: one layer, prompt of {P} tokens into an empty cache, "
+                                   f"batch {cfg.batch} x {cfg.heads} heads x {cfg.head_dim} {cfg.dtype}, budget {cfg.budget}"},
+            "value": round(cfg.batch * P / (ms * 1e-3), 1), "unit": "prompt tokens/s per layer", "ms": round(ms, 3),
+            "roofline": {"bound": "mfma", "achieved": round(flops / (ms * 1e-3) / 1e12, 2), "peak": 78.6,
+                         "unit": "TFLOP/s", "frac": round(flops / (ms * 1e-3) / 1e12 / 78.6, 4), "traffic": None,
+                         "kernel": "wkv_prefill_rows + wkv_prefill_scores + wkv_prefill_compress (one wkv_prefill call)",
+                         "flops_per_call": flops,
+                         "note": "algorithmic flops (q.K^T and P.V once each) over the whole call, against the fp64 "
+                                 "MFMA peak: the logits are contracted in fp64, and twice (rows, then column sums)"},
+        }
+        del tq, tk, tv, out
+        torch.cuda.empty_cache()
 
     if not args.skip_cpu_baseline:
         import oracle

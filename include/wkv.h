@@ -50,7 +50,7 @@ extern "C" {
 
 /* limits of this build */
 #define WKV_MAX_BUDGET 4095   /* slots per unit, bounded by the LDS staging of one score row */
-#define WKV_MAX_PROMPT 8192   /* tokens wkv_prefill takes at once, bounded by the LDS staging of their scores */
+#define WKV_MAX_PROMPT 4096   /* tokens wkv_prefill takes at once, bounded by the LDS staging of their scores */
 
 /* which entries may be ranked / how the victim's value is treated (wkv_options) */
 #define WKV_SCORE_AVERAGE    0   /* abar = a / n: WeightedKV (Algorithm 1)                         */
@@ -120,7 +120,8 @@ int wkv_step(wkv_handle* h, const void* q, const void* k_new, const void* v_new,
  *   - the score list Algorithm 1's bookkeeping accumulates over these rows: a_i = sum_t A_t[i],
  *     n_i = n_tokens - i;
  *   - while more than `budget` entries remain: Algorithm 1's selection and merge with these
- *     (fixed) scores, protected entries as in wkv_step.
+ *     (fixed) scores, protected entries as in wkv_step; merged rows are rounded to the cache
+ *     dtype once, when the compression is over.
  * For n_tokens <= budget + 1 the result is that of n_tokens calls of wkv_step; beyond that it
  * is a different function (a streamed token attends to an already compressed cache).
  *   q, k, v : DEVICE pointers, contiguous [n_tokens, batch, heads, head_dim] in the handle's
@@ -128,7 +129,7 @@ int wkv_step(wkv_handle* h, const void* q, const void* k_new, const void* v_new,
  *   out     : DEVICE pointer of the same shape, or NULL if the outputs are not wanted.
  * Built for 16-bit caches with head_dim 64 or 128 and the average or cumulative scoring rule
  * (WKV_ESIZE / WKV_EINVAL otherwise); 1 <= n_tokens <= WKV_MAX_PROMPT.  Allocates and frees its
- * own device scratch (16 bytes per token and unit, plus a copy of v when values are merged)
+ * own device scratch (16 bytes per token and unit)
  * and returns when the work on `stream` has completed.  The eviction log is not written.
  * On error the cache is unchanged, except for WKV_EHIP after the launch.
  */

@@ -74,7 +74,8 @@ class BruteUnit:
         """Bulk prefill of the empty cache with a prompt (lists of d-lists).  Reading (the paper
         has no such procedure): causal attention over the uncompressed prompt, the scores that
         Algorithm 1's bookkeeping would accumulate over those rows, then selection and merge
-        repeated until m entries remain, with no attention in between.
+        repeated until m entries remain, with no attention in between; merged rows are rounded to
+        the cache format once, when the compression is over.
         Returns (outputs, removed tokens in order)."""
         assert self.t == 0
         d, P = self.d, len(Q)
@@ -99,12 +100,12 @@ class BruteUnit:
                 den = abar[j] + abar[j + 1]
                 merged = [(abar[j] * self.V[j][c] + abar[j + 1] * self.V[j + 1][c]) / den if den > 0
                           else 0.5 * self.V[j][c] + 0.5 * self.V[j + 1][c] for c in range(d)]
-                if self.rounder is not None:
-                    merged = [self.rounder(x) for x in merged]
-                self.V[j + 1] = merged
+                self.V[j + 1] = merged                                   # not rounded: never stored as such
                 self.nmerged[j + 1] += self.nmerged[j]
             removed.append(self.pos[j])
             for lst in (self.K, self.V, self.a, self.n, self.pos, self.nmerged):
                 del lst[j]
+        if self.rounder is not None:                                     # rows enter the cache: one rounding
+            self.V = [[self.rounder(x) for x in row] for row in self.V]
         self.t = P
         return outs, removed

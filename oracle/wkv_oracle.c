@@ -299,7 +299,10 @@ int orc_run(orc_t *o, int nsteps, const float *q, const float *k, const float *v
  * the score list is what Algorithm 1's bookkeeping accumulates over those rows, a_i = sum_t
  * A_t[i], n_i = P - i (rows that attended token i); then, while more than m entries remain,
  * the selection and merge of Algorithm 1 are repeated with those scores (no new attention
- * between two merges; the survivor keeps its own a and n, so every abar is fixed).  This is
+ * between two merges; the survivor keeps its own a and n, so every abar is fixed).  None of
+ * the intermediate rows of this compression is ever held in the cache, so the merges are
+ * carried out in fp64 and a row is rounded to the storage format once, when it enters the
+ * cache (the paper names no number format).  This is
  * NOT the same function as feeding the prompt token by token, where every token beyond the
  * m-th attends to an already compressed cache; the two coincide for P <= m + 1.
  *
@@ -353,7 +356,7 @@ int orc_prefill(orc_t *o, int P, const float *q, const float *k, const float *v,
             if (runner_up) runner_up[(size_t)e * U + iu] = second;
             if (o->merge_mode == 0) {
                 double *Vj = V + (size_t)idx[j] * d, *Vr = V + (size_t)idx[j + 1] * d;
-                orc_merge_pair(score[j], score[j + 1], Vj, Vr, d, o->storage, Vr);
+                orc_merge_pair(score[j], score[j + 1], Vj, Vr, d, -1, Vr);     /* fp64, not rounded yet */
                 nm[j + 1] += nm[j];
             }
             int tail = L - 1 - j;
@@ -365,7 +368,8 @@ int orc_prefill(orc_t *o, int P, const float *q, const float *k, const float *v,
         }
         for (int i = 0; i < L; ++i) {
             memcpy(u->K + (size_t)i * d, K + (size_t)idx[i] * d, sizeof(double) * d);
-            memcpy(u->V + (size_t)i * d, V + (size_t)idx[i] * d, sizeof(double) * d);
+            for (int c = 0; c < d; ++c)                                         /* the row enters the cache */
+                u->V[(size_t)i * d + c] = orc_round_storage(V[(size_t)idx[i] * d + c], o->storage);
             u->a[i] = a[i]; u->n[i] = n[i]; u->pos[i] = idx[i]; u->nmerged[i] = nm[i];
         }
         u->L = L; u->t = P;

@@ -22,7 +22,7 @@ LIB_PATH = os.path.join(_HERE, "libwkv.so")
 WKV_FP32, WKV_FP16, WKV_BF16 = 0, 1, 2
 WKV_OK, WKV_EINVAL, WKV_ENOMEM, WKV_EHIP, WKV_ESIZE = 0, -1, -2, -3, -4
 WKV_MAX_BUDGET = 4095
-WKV_MAX_PROMPT = 8192
+WKV_MAX_PROMPT = 4096
 WKV_SCORE_AVERAGE, WKV_SCORE_CUMULATIVE, WKV_SCORE_LAST = 0, 1, 2
 WKV_MERGE_CONVEX, WKV_MERGE_NONE = 0, 1
 (WKV_STEP, WKV_LEN, WKV_K, WKV_V, WKV_SCORE_SUM, WKV_COUNT, WKV_POS, WKV_NMERGED,

@@ -274,24 +274,18 @@ int wkv_prefill(wkv_handle* h, const void* q, const void* k, const void* v, void
                     wkv_prefill_lds_bytes(n_tokens), lds_max);
 
     const size_t units = h->c.units, P = (size_t)n_tokens;
-    const size_t rowb = (size_t)o.head_dim * dtype_bytes(o.dtype);
-    const bool need_vw = o.merge_mode == WKV_MERGE_CONVEX && n_tokens > o.budget;
     double *lse = nullptr, *a = nullptr;
-    void* vw = nullptr;
     e = hipMalloc((void**)&lse, units * P * sizeof(double));
     if (e == hipSuccess) e = hipMalloc((void**)&a, units * P * sizeof(double));
-    if (e == hipSuccess && need_vw) e = hipMalloc(&vw, units * P * rowb);
     if (e != hipSuccess) {
         (void)hipGetLastError();
         if (lse) (void)hipFree(lse);
-        if (a) (void)hipFree(a);
         return fail(e == hipErrorOutOfMemory ? WKV_ENOMEM : WKV_EHIP, "scratch for a prompt of %d tokens: %s",
                     n_tokens, hipGetErrorString(e));
     }
-    e = wkv_launch_prefill(h->c, o.dtype, o.head_dim, q, k, v, out, lse, a, vw, n_tokens, (hipStream_t)stream);
+    e = wkv_launch_prefill(h->c, o.dtype, o.head_dim, q, k, v, out, lse, a, n_tokens, (hipStream_t)stream);
     const hipError_t e2 = hipStreamSynchronize((hipStream_t)stream);
     (void)hipFree(lse); (void)hipFree(a);
-    if (vw) (void)hipFree(vw);
     if (e != hipSuccess) return fail(WKV_EHIP, "kernel launch: %s", hipGetErrorString(e));
     if (e2 != hipSuccess) return fail(WKV_EHIP, "hipStreamSynchronize: %s", hipGetErrorString(e2));
     h->t = n_tokens;

@@ -70,11 +70,9 @@ hipError_t wkv_split_prepare(int dtype, int head_dim, size_t lds);
 
 
 // ---- bulk prefill of an empty cache (wkv_prefill.hip).  q, k, v, out: [P][units][D] device
-// memory (out may be null); lse, a: [units][P] fp64 scratch; vw: [units][P][D] scratch in the
-// cache dtype (used when values are merged and P exceeds the budget).  16-bit caches, D in {64,128}.
+// memory (out may be null); lse, a: [units][P] fp64 scratch.  16-bit caches, D in {64,128}.
 hipError_t wkv_launch_prefill(const WkvCache& c, int dtype, int head_dim, const void* q, const void* k,
-                              const void* v, void* out, double* lse, double* a, void* vw, int P,
-                              hipStream_t stream);
+                              const void* v, void* out, double* lse, double* a, int P, hipStream_t stream);
 size_t wkv_prefill_lds_bytes(int P);
 
 #endif

@@ -22,8 +22,8 @@
 //      sums stay in registers, no atomics, fixed order.
 //   3. wkv_prefill_compress: one workgroup per unit: rank of every candidate by (score, token),
 //      the P - m lowest are removed; survivors are laid out in token order in the cache; every
-//      run of removed tokens is folded into the survivor on its right in ascending score order,
-//      exactly the sequence of merges the repeated selection would perform.
+//      run of removed tokens is folded into the survivor on its right with the weights that the
+//      sequence of pairwise merges in ascending score order gives each raw row.
 //
 // MFMA operand layouts (one wave; g = lane / 16, x = lane % 16), as measured on gfx950:
 //   both: A operand = A[row x][k = g], B operand = B[k = g][column x];
@@ -40,6 +40,7 @@ typedef double double4_t __attribute__((ext_vector_type(4)));
 typedef float  float4_t  __attribute__((ext_vector_type(4)));
 
 constexpr int TILE = 16;
+constexpr int WKV_PREFILL_MAX_TOKENS = 4096;   // prompt length the compression stages in LDS (WKV_MAX_PROMPT)
 
 // element e of a row fragment held as raw 32-bit words (two 16-bit elements per word)
 template <class TT> __device__ __forceinline__ float frag_elem(const uint32_t* w, int e) {
@@ -55,13 +56,15 @@ template <class TT> __device__ __forceinline__ float frag_elem(const uint32_t* w
 __device__ __forceinline__ double xor_max(double v, int mask) { return fmax(v, __shfl_xor(v, mask)); }
 
 // S^T tile: rows = 16 keys, columns = 16 queries; register r of lane (g, x) = key g + 4r, query x.
+// Both operands are the exact storage values; the softmax scale is applied to the four results.
 template <class TT, int D>
 __device__ __forceinline__ double4_t logits_tile(const uint32_t (&kfrag)[D / 8], const double (&qd)[D / 4]) {
     double4_t s = {0.0, 0.0, 0.0, 0.0};
 #pragma unroll
     for (int kk = 0; kk < D / 4; ++kk)
         s = __builtin_amdgcn_mfma_f64_16x16x4f64((double)frag_elem<TT>(kfrag, kk), qd[kk], s, 0, 0, 0);
-    return s;
+    const double scale = 1.0 / sqrt((double)D);
+    return s * scale;
 }
 
 // ------------------------------------------------------------------ 1. rows
@@ -92,9 +95,8 @@ void wkv_prefill_rows(const void* __restrict__ q_, const void* __restrict__ k_, 
         const int tq = min(qt * TILE + x, P - 1);
         uint32_t w[CH / 2];
         load_words<CH / 2>(qb + (size_t)tq * tok + g * CH * TT::BYTES, w);
-        const double scale = 1.0 / sqrt((double)D);
 #pragma unroll
-        for (int e = 0; e < CH; ++e) qd[e] = (double)frag_elem<TT>(w, e) * scale;
+        for (int e = 0; e < CH; ++e) qd[e] = (double)frag_elem<TT>(w, e);
     }
     double mrow = -INFINITY, lrow = 0.0;      // running maximum and sum of query x (same in the 4 lanes x, x+16, ...)
     constexpr int NE = D / 16;                // output column sets: lane (g, x) owns columns NE*x .. NE*x+NE-1
@@ -102,15 +104,26 @@ void wkv_prefill_rows(const void* __restrict__ q_, const void* __restrict__ k_, 
 #pragma unroll
     for (int e = 0; e < NE; ++e) o[e] = float4_t{0.f, 0.f, 0.f, 0.f};
 
-    for (int kt = 0; kt <= qt; ++kt) {
-        // K fragment: key 16 kt + x, the same quarter of the row as the query fragment
-        uint32_t kfrag[CH / 2];
-        load_words<CH / 2>(kb + (size_t)min(kt * TILE + x, P - 1) * tok + g * CH * TT::BYTES, kfrag);
-        // V fragments: keys 16 kt + g + 4r, columns NE*x .. NE*x+NE-1
-        uint32_t vfrag[4][NE / 2];
+    // K fragment of a key tile: key 16 kt + x, the same quarter of the row as the query fragment.
+    // V fragments: keys 16 kt + g + 4r, columns NE*x .. NE*x+NE-1.  The fragments of the next tile are
+    // requested before the current tile is worked on.
+    uint32_t knext[CH / 2], vnext[4][NE / 2];
+    auto request = [&](int kt) {
+        load_words<CH / 2>(kb + (size_t)min(kt * TILE + x, P - 1) * tok + g * CH * TT::BYTES, knext);
 #pragma unroll
         for (int r = 0; r < 4; ++r)
-            load_words<NE / 2>(vb + (size_t)min(kt * TILE + g + 4 * r, P - 1) * tok + x * NE * TT::BYTES, vfrag[r]);
+            load_words<NE / 2>(vb + (size_t)min(kt * TILE + g + 4 * r, P - 1) * tok + x * NE * TT::BYTES, vnext[r]);
+    };
+    request(0);
+    for (int kt = 0; kt <= qt; ++kt) {
+        uint32_t kfrag[CH / 2], vfrag[4][NE / 2];
+#pragma unroll
+        for (int w = 0; w < CH / 2; ++w) kfrag[w] = knext[w];
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+#pragma unroll
+            for (int w = 0; w < NE / 2; ++w) vfrag[r][w] = vnext[r][w];
+        request(min(kt + 1, qt));                             // the last request repeats a tile, unused
 
         double4_t s = logits_tile<TT, D>(kfrag, qd);
         if (kt == qt) {                       // the diagonal tile: key g + 4r may be attended by query x only if <= x
@@ -181,27 +194,47 @@ void wkv_prefill_scores(const void* __restrict__ q_, const void* __restrict__ k_
     const size_t tok = (size_t)units * ROWB;
     const char* qb = reinterpret_cast<const char*>(q_) + (size_t)u * ROWB;
     const char* kb = reinterpret_cast<const char*>(k_) + (size_t)u * ROWB;
-    const double scale = 1.0 / sqrt((double)D);
 
     uint32_t kfrag[CH / 2];
     load_words<CH / 2>(kb + (size_t)min(kt * TILE + x, P - 1) * tok + g * CH * TT::BYTES, kfrag);
     double acc[4] = {0.0, 0.0, 0.0, 0.0};
-    for (int qt = kt; qt < ntiles; ++qt) {
-        const int tq = qt * TILE + x;
-        const int tqc = min(tq, P - 1);
-        uint32_t w[CH / 2];
-        load_words<CH / 2>(qb + (size_t)tqc * tok + g * CH * TT::BYTES, w);
-        const double l = lse[(size_t)u * P + tqc];
+    uint32_t wnext[CH / 2];
+    double lnext;
+    auto request = [&](int qt) {
+        const int tqc = min(qt * TILE + x, P - 1);
+        load_words<CH / 2>(qb + (size_t)tqc * tok + g * CH * TT::BYTES, wnext);
+        lnext = lse[(size_t)u * P + tqc];
+    };
+    // Software pipeline: the MFMA chain of the next query tile is issued in the same stretch of
+    // straight-line code as the exponentials of the current one, so the matrix unit and the
+    // vector unit of a SIMD work at the same time.  (Waves left to themselves run in lockstep --
+    // all in their MFMA chain, then all in their exponentials -- and the two units take turns.)
+    request(kt);
+    double4_t s_cur;
+    double l_cur = lnext;
+    {
         double qd[CH];
 #pragma unroll
-        for (int e = 0; e < CH; ++e) qd[e] = (double)frag_elem<TT>(w, e) * scale;
-        const double4_t s = logits_tile<TT, D>(kfrag, qd);
+        for (int e = 0; e < CH; ++e) qd[e] = (double)frag_elem<TT>(wnext, e);
+        request(min(kt + 1, ntiles - 1));
+        s_cur = logits_tile<TT, D>(kfrag, qd);
+    }
+    for (int qt = kt; qt < ntiles; ++qt) {
+        const int tq = qt * TILE + x;
+        double qd[CH];
+#pragma unroll
+        for (int e = 0; e < CH; ++e) qd[e] = (double)frag_elem<TT>(wnext, e);
+        const double l_next = lnext;
+        request(min(qt + 2, ntiles - 1));
+        const double4_t s_next = logits_tile<TT, D>(kfrag, qd);           // tile qt + 1 (a repeat on the last round)
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
             const int key = kt * TILE + g + 4 * r;
             const bool on = tq < P && key <= tq;                           // causal, and inside the prompt
-            acc[r] += on ? exp(s[r] - l) : 0.0;
+            acc[r] += exp(on ? s_cur[r] - l_cur : -INFINITY);              // exp(-inf) = 0; no branch
         }
+        s_cur = s_next;
+        l_cur = l_next;
     }
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
@@ -212,12 +245,26 @@ void wkv_prefill_scores(const void* __restrict__ q_, const void* __restrict__ k_
 }
 
 // ------------------------------------------------------------------ 3. compress
-// One workgroup per unit.  sc[] (LDS, fp64) holds the score of every token; fl[] one byte per
-// token: 1 = removed.  Afterwards the same LDS holds, as int32, the right neighbour links.
+// One workgroup per unit.  Scores are fixed during the compression, so the P - L tokens that
+// the repeated selection removes are the candidates of lowest (score, token), in that order.
+//
+// Values.  A removed token j folds into the nearest token on its right that is still present
+// when its turn comes, i.e. the nearest one with a higher rank (survivors rank above everything):
+// its parent.  The merges therefore form a forest whose roots are the survivors, and a node
+// receives its children in ascending rank.  With s the scores, a child c of p contributes
+//     g_c * prod_{children c' of p ranked after c} f_c',   f_c' = s_p / (s_c' + s_p),  g_c = s_c / (s_c + s_p)
+// of its accumulated value to p's, and p's own raw value keeps prod_{children} f_c'.  The weight
+// of a raw token in its survivor's row is the product of these coefficients up the tree, and the
+// row is the weighted sum of the raw rows of the run -- the same numbers as the sequence of pairwise
+// merges (Algorithm 1) in fp64, with no dependent chain of row updates.  Rows are rounded to the
+// cache format once, when they are written.
+//
+// LDS: sc[P] score, later weight | ae[P] edge coefficient | a0[P] own coefficient | slot[P] |
+//      wcnt[NT] | rk[P] rank (16 bit) | par[P] parent (16 bit).
 template <class TT, int D>
 __global__ __launch_bounds__(1024)
 void wkv_prefill_compress(WkvCache c, const void* __restrict__ k_, const void* __restrict__ v_,
-                          void* __restrict__ vw_, const double* __restrict__ a, int P)
+                          const double* __restrict__ a, int P)
 {
     constexpr int ROWB = D * TT::BYTES;
     constexpr int EPW = (D + 63) / 64;
@@ -234,9 +281,14 @@ void wkv_prefill_compress(WkvCache c, const void* __restrict__ k_, const void* _
     const double* ap = a + (size_t)u * P;
 
     extern __shared__ double lds[];
-    double*  sc = lds;                                        // [P]
-    int32_t* slot = reinterpret_cast<int32_t*>(sc + P);       // [P] slot of a survivor, -1 for a removed token
-    int32_t* wcnt = slot + P;                                 // [NT] scan scratch
+    double*   sc   = lds;
+    double*   ae   = sc + P;
+    double*   a0   = ae + P;
+    int32_t*  slot = reinterpret_cast<int32_t*>(a0 + P);      // slot of a survivor, -1 for a removed token
+    int32_t*  wcnt = slot + P;
+    uint16_t* rk   = reinterpret_cast<uint16_t*>(wcnt + NT);
+    uint16_t* par  = rk + P;
+    constexpr int TOP = 0x10000;                              // a survivor ranks above every removed token
     const int L = (P < m) ? P : m;
     const int nrem = P - L;                                   // tokens to remove
     const int lo = c.n_sink, hi = P - c.R;                    // candidates: lo <= token < hi
@@ -250,17 +302,18 @@ void wkv_prefill_compress(WkvCache c, const void* __restrict__ k_, const void* _
     __syncthreads();
     // rank among the candidates by (score, token); the nrem lowest are removed
     for (int i = tid; i < P; i += NT) {
-        int removed = 0;
+        int rank = 0xFFFF;
         if (nrem > 0 && i >= lo && i < hi) {
             const double si = sc[i];
-            int rank = 0;
+            rank = 0;
             for (int k = lo; k < hi; ++k) {
                 const double sk = sc[k];
                 rank += (sk < si || (sk == si && k < i)) ? 1 : 0;
             }
-            removed = rank < nrem;
+            if (rank >= nrem) rank = 0xFFFF;
         }
-        slot[i] = removed ? -1 : 0;
+        rk[i] = (uint16_t)rank;
+        slot[i] = (rank != 0xFFFF) ? -1 : 0;
     }
     __syncthreads();
     // survivors get consecutive slots in token order: exclusive scan over the keep flags
@@ -291,98 +344,175 @@ void wkv_prefill_compress(WkvCache c, const void* __restrict__ k_, const void* _
             if (col < D) store_bits<TT>(Kc + (size_t)sidx * ROWB, col, load_bits<TT>(kb + (size_t)i * tok, col));
         }
     }
-    // values.  A survivor at token i with previous survivor at token i0 receives the removed tokens
-    // i0+1 .. i-1, one after the other in ascending (score, token) order; each folds into whatever is
-    // then its right neighbour (a still present token of the run, or the survivor).  One wave per
-    // run; vw_ is a working copy of V ([units][P][D]) whose rows are rewritten in place.
-    char* vw = reinterpret_cast<char*>(vw_) + (size_t)u * P * ROWB;
-    const bool merging = c.merge_mode == 0;
-    __syncthreads();
-    for (int i = wid; i < P; i += NW) {
-        const int sidx = slot[i];
-        if (sidx < 0) continue;
-        int i0 = i - 1;
-        while (i0 >= 0 && slot[i0] < 0) --i0;                  // previous survivor (or -1)
-        const int len = i - 1 - i0;                            // removed tokens i0+1 .. i-1
-        if (merging && len > 0) {
-            // process the run in ascending (score, token): repeated arg-min over what is left;
-            // a processed token is marked in slot[] with -2 (only this wave touches the run)
-            for (int step = 0; step < len; ++step) {
-                Best b = { INFINITY, NONE_POS, -1 };
-                for (int j = i0 + 1 + lane; j < i; j += 64)
-                    if (slot[j] == -1 && better(sc[j], j, b)) b = { sc[j], j, j };
-                b = wave_argmin(b);
-                const int j = b.phys;
-                if (j < 0) break;                              // cannot happen: len tokens are pending
-                int r = j + 1;
-                while (slot[r] == -2) ++r;                     // right neighbour still present (r <= i)
-                const double sj = sc[j], sr = sc[r];
-                const double den = sj + sr;
-                const bool zero_den = !(den > 0.0);
+
+    const bool merging = c.merge_mode == 0 && nrem > 0;
+    if (merging) {
+        // parent of a removed token: the nearest token to its right that outranks it
+        for (int i = tid; i < P; i += NT) {
+            int k = i;
+            if (slot[i] < 0) { const int ri = rk[i]; k = i + 1; while (slot[k] < 0 && rk[k] < ri) ++k; }
+            par[i] = (uint16_t)k;                             // a survivor is its own parent
+        }
+        __syncthreads();
+        // coefficients.  First f of every removed token with respect to its parent (one division per
+        // token, kept in ae[]); then the products over children and over later siblings, which are
+        // multiplications only -- a survivor that takes in thousands of tokens has as many children,
+        // and each of them looks at all the others.  The children of p sit in the stretch left of p
+        // that p outranks.
+        for (int i = tid; i < P; i += NT) {
+            if (slot[i] >= 0) continue;
+            const double sp = sc[par[i]], den = sc[i] + sp;
+            ae[i] = (den > 0.0) ? sp / den : 0.5;
+            if (!(den > 0.0)) atomicAdd(&c.status[0], 1);
+        }
+        __syncthreads();
+        constexpr int MAXTOK = (WKV_PREFILL_MAX_TOKENS + 1023) / 1024;   // tokens per thread
+        double edge[MAXTOK];
 #pragma unroll
-                for (int e = 0; e < EPW; ++e) {
-                    const int col = lane + 64 * e;
-                    if (col < D) {
-                        const double vj = (double)load_elem<TT>(vw + (size_t)j * ROWB, col);
-                        const double vr = (double)load_elem<TT>(vw + (size_t)r * ROWB, col);
-                        const double y = zero_den ? 0.5 * vj + 0.5 * vr : (sj * vj + sr * vr) / den;
-                        store_elem_f64<TT>(vw + (size_t)r * ROWB, col, y);
-                    }
-                }
-                if (lane == 0 && zero_den) atomicAdd(&c.status[0], 1);
-                if (lane == 0) slot[j] = -2;
-                __builtin_amdgcn_s_waitcnt(0);                 // the row just written is read again by a later merge
+        for (int kk = 0; kk < MAXTOK; ++kk) {
+            const int i = tid + kk * NT;
+            edge[kk] = 0.0;
+            if (i >= P) continue;
+            const bool removed = slot[i] < 0;
+            {   // own coefficient of token i: product of f over its children
+                const int ri = removed ? (int)rk[i] : TOP;
+                double prod = 1.0;
+                for (int k = i - 1; k >= 0 && slot[k] < 0 && rk[k] < ri; --k)
+                    if (par[k] == i) prod *= ae[k];
+                a0[i] = prod;
+            }
+            if (removed) {   // edge coefficient of token i within its parent: g_i times f of the later siblings
+                const int p = par[i], ri = rk[i];
+                const int rp = (slot[p] < 0) ? (int)rk[p] : TOP;
+                const double sp = sc[p], si = sc[i], den = si + sp;
+                double prod = (den > 0.0) ? si / den : 0.5;
+                for (int k = p - 1; k >= 0 && slot[k] < 0 && rk[k] < rp; --k)
+                    if (par[k] == p && rk[k] > ri) prod *= ae[k];
+                edge[kk] = prod;
             }
         }
-        const char* src = (merging && P > m) ? vw + (size_t)i * ROWB : vb + (size_t)i * tok;
+        __syncthreads();
+#pragma unroll
+        for (int kk = 0; kk < MAXTOK; ++kk) {
+            const int i = tid + kk * NT;
+            if (i < P && slot[i] < 0) ae[i] = edge[kk];
+        }
+        __syncthreads();
+        // weight of every removed token's raw value in its survivor's row (scores are no longer needed)
+        for (int i = tid; i < P; i += NT) {
+            if (slot[i] >= 0) continue;
+            double w = ae[i] * a0[i];
+            for (int q = par[i]; slot[q] < 0; q = par[q]) w *= ae[q];
+            sc[i] = w;
+        }
+        __syncthreads();
+    }
+    // acc += sum over rows k = first, first + stride, ... <= last of weight(k) * V_k, where the last
+    // row of a run is the survivor itself (own coefficient).  Eight rows are requested at a time:
+    // the sum is a chain of dependent FMAs, the loads need not be.
+    auto weighted_rows = [&](double (&acc)[EPW], int first, int last, int stride) {
+        for (int k0 = first; k0 <= last; k0 += 8 * stride) {
+            uint32_t raw[8][EPW];
+            double w[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const int k = k0 + j * stride;
+                const int kc = min(k, last);
+                w[j] = (k > last) ? 0.0 : (k < last) ? sc[kc] : a0[last];
+#pragma unroll
+                for (int e = 0; e < EPW; ++e)
+                    raw[j][e] = load_bits<TT>(vb + (size_t)kc * tok, min(lane + 64 * e, D - 1));
+            }
+#pragma unroll
+            for (int j = 0; j < 8; ++j)
+#pragma unroll
+                for (int e = 0; e < EPW; ++e) acc[e] = fma(w[j], (double)bits_elem<TT>(raw[j][e]), acc[e]);
+        }
+    };
+    // values of the survivors.  rk[] is free now: it takes the number of tokens that fold into a survivor.
+    constexpr int LONG = 32;                                  // runs from this length on are summed by the whole workgroup
+    const bool coop = merging && P >= NW * D;                 // (the partial sums borrow ae[], P doubles)
+    for (int i = tid; i < P; i += NT) {
+        if (slot[i] < 0) continue;
+        int i0 = i - 1;
+        while (i0 >= 0 && slot[i0] < 0) --i0;                  // previous survivor (or -1)
+        rk[i] = (uint16_t)(merging ? i - 1 - i0 : 0);
+    }
+    __syncthreads();
+    for (int i = wid; i < P; i += NW) {                       // short runs: one wave per survivor
+        const int sidx = slot[i];
+        if (sidx < 0) continue;
+        const int len = rk[i];
+        if (coop && len >= LONG) continue;
+        const char* own = vb + (size_t)i * tok;
+        if (len == 0) {                                        // nothing folds into this token
+#pragma unroll
+            for (int e = 0; e < EPW; ++e) {
+                const int col = lane + 64 * e;
+                if (col < D) store_bits<TT>(Vc + (size_t)sidx * ROWB, col, load_bits<TT>(own, col));
+            }
+            continue;
+        }
+        double acc[EPW];
+#pragma unroll
+        for (int e = 0; e < EPW; ++e) acc[e] = 0.0;
+        weighted_rows(acc, i - len, i, 1);
 #pragma unroll
         for (int e = 0; e < EPW; ++e) {
             const int col = lane + 64 * e;
-            if (col < D) store_bits<TT>(Vc + (size_t)sidx * ROWB, col, load_bits<TT>(src, col));
+            if (col < D) store_elem_f64<TT>(Vc + (size_t)sidx * ROWB, col, acc[e]);
         }
     }
-}
-
-// copies v [P][units][D] into the working layout [units][P][D]
-template <int ROWB>
-__global__ void wkv_prefill_copy_v(const void* __restrict__ v_, void* __restrict__ vw_, int P, int units)
-{
-    const size_t n16 = (size_t)P * units * (ROWB / 16);
-    for (size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x; idx < n16; idx += (size_t)gridDim.x * blockDim.x) {
-        const size_t part = idx % (ROWB / 16), row = idx / (ROWB / 16);
-        const size_t t = row / units, u = row % units;
-        reinterpret_cast<uint4*>(vw_)[(u * P + t) * (ROWB / 16) + part] = reinterpret_cast<const uint4*>(v_)[idx];
+    if (coop) {                                                // long runs: every wave takes every NW-th row
+        double* part = ae;                                     // [NW][D]
+        for (int i = 0; i < P; ++i) {                          // uniform over the workgroup
+            if (slot[i] < 0 || rk[i] < LONG) continue;
+            const int len = rk[i];
+            double acc[EPW];
+#pragma unroll
+            for (int e = 0; e < EPW; ++e) acc[e] = 0.0;
+            weighted_rows(acc, i - len + wid, i, NW);
+            __syncthreads();                                   // the previous long run's partial sums have been read
+#pragma unroll
+            for (int e = 0; e < EPW; ++e) {
+                const int col = lane + 64 * e;
+                if (col < D) part[wid * D + col] = acc[e];
+            }
+            __syncthreads();
+            if (tid < D) {
+                double y = 0.0;
+                for (int w = 0; w < NW; ++w) y += part[w * D + tid];
+                store_elem_f64<TT>(Vc + (size_t)slot[i] * ROWB, tid, y);
+            }
+        }
     }
 }
 
 template <class TT, int D>
 hipError_t run(const WkvCache& c, const void* q, const void* k, const void* v, void* out,
-               double* lse, double* a, void* vw, int P, hipStream_t stream)
+               double* lse, double* a, int P, hipStream_t stream)
 {
     const int ntiles = (P + TILE - 1) / TILE, groups = (ntiles + 3) / 4;
     hipLaunchKernelGGL((wkv_prefill_rows<TT, D>), dim3(c.units * groups), dim3(256), 0, stream, q, k, v, out, lse, P, c.units);
     hipLaunchKernelGGL((wkv_prefill_scores<TT, D>), dim3(c.units * groups), dim3(256), 0, stream, q, k, lse, a, P, c.units);
-    if (c.merge_mode == 0 && P > c.m)
-        hipLaunchKernelGGL((wkv_prefill_copy_v<D * TT::BYTES>), dim3(2048), dim3(256), 0, stream, v, vw, P, c.units);
     const size_t lds = wkv_prefill_lds_bytes(P);
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&wkv_prefill_compress<TT, D>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL((wkv_prefill_compress<TT, D>), dim3(c.units), dim3(1024), lds, stream, c, k, v, vw, a, P);
+    hipLaunchKernelGGL((wkv_prefill_compress<TT, D>), dim3(c.units), dim3(1024), lds, stream, c, k, v, a, P);
     return hipGetLastError();
 }
 
 }  // namespace
 
-size_t wkv_prefill_lds_bytes(int P) { return (size_t)P * 12 + 1024 * 4; }
+size_t wkv_prefill_lds_bytes(int P) { return (size_t)P * 32 + 1024 * 4; }
 
 hipError_t wkv_launch_prefill(const WkvCache& c, int dtype, int head_dim, const void* q, const void* k,
-                              const void* v, void* out, double* lse, double* a, void* vw, int P,
-                              hipStream_t stream)
+                              const void* v, void* out, double* lse, double* a, int P, hipStream_t stream)
 {
-    if (dtype == 1 && head_dim == 64)  return run<TF16, 64>(c, q, k, v, out, lse, a, vw, P, stream);
-    if (dtype == 1 && head_dim == 128) return run<TF16, 128>(c, q, k, v, out, lse, a, vw, P, stream);
-    if (dtype == 2 && head_dim == 64)  return run<TBF16, 64>(c, q, k, v, out, lse, a, vw, P, stream);
-    if (dtype == 2 && head_dim == 128) return run<TBF16, 128>(c, q, k, v, out, lse, a, vw, P, stream);
+    if (dtype == 1 && head_dim == 64)  return run<TF16, 64>(c, q, k, v, out, lse, a, P, stream);
+    if (dtype == 1 && head_dim == 128) return run<TF16, 128>(c, q, k, v, out, lse, a, P, stream);
+    if (dtype == 2 && head_dim == 64)  return run<TBF16, 64>(c, q, k, v, out, lse, a, P, stream);
+    if (dtype == 2 && head_dim == 128) return run<TBF16, 128>(c, q, k, v, out, lse, a, P, stream);
     return hipErrorInvalidValue;
 }
