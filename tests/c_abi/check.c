@@ -4,7 +4,9 @@
  * equal to one constant vector, every output and every (merged) cached value equals that
  * vector; the cache holds min(tokens, budget) slots; token positions are strictly increasing
  * and end at the newest token; merge counts sum to the number of tokens; the eviction log
- * names tokens outside the recent window.  Prints "c_abi ok" and exits 0 on success.
+ * names tokens outside the recent window.  Then the same facts for a prompt that goes through
+ * wkv_prefill into an fp16 cache, followed by one decode step.  Prints "c_abi ok" and exits 0
+ * on success.
  */
 #include <hip/hip_runtime_api.h>
 #include <math.h>
@@ -24,6 +26,25 @@
 #define HIP(x) do { hipError_t e_ = (x); if (e_ != hipSuccess) { printf("hip: %s (line %d)\n", hipGetErrorString(e_), __LINE__); return 2; } } while (0)
 #define WKV(x) do { int r_ = (x); if (r_ != WKV_OK) { printf("wkv: %d %s (line %d)\n", r_, wkv_last_error(), __LINE__); return 3; } } while (0)
 #define CHECK(c) do { if (!(c)) { printf("check failed: %s (line %d)\n", #c, __LINE__); return 4; } } while (0)
+
+/* values k/64 with |k| <= 64 are exact in fp16: sign, exponent, 10 fraction bits, no rounding needed */
+static uint16_t half_of_64th(int k)
+{
+    if (k == 0) return 0;
+    const uint16_t sign = k < 0 ? 0x8000 : 0;
+    unsigned a = (unsigned)(k < 0 ? -k : k);          /* value = a / 64, 1 <= a <= 64 */
+    int e = 0;
+    while ((a >> e) > 1) ++e;                          /* leading bit of a */
+    const unsigned frac = (a << (10 - e)) & 0x3FF;     /* bits below the leading one, left aligned */
+    return (uint16_t)(sign | ((unsigned)(e - 6 + 15) << 10) | frac);
+}
+static float half_value(uint16_t h)
+{
+    const int e = (h >> 10) & 31;
+    const float m = (float)(h & 0x3FF) / 1024.0f;
+    const float v = e ? ldexpf(1.0f + m, e - 15) : ldexpf(m, -14);
+    return (h & 0x8000) ? -v : v;
+}
 
 static float lcg(unsigned* s) { *s = *s * 1664525u + 1013904223u; return ((*s >> 8) & 0xFFFF) / 32768.0f - 1.0f; }
 
@@ -81,6 +102,55 @@ int main(void)
     WKV(wkv_destroy(h));
     HIP(hipFree(dq)); HIP(hipFree(dk)); HIP(hipFree(dv)); HIP(hipFree(dout));
     free(hq); free(hk); free(hv); free(ho);
+
+    /* ---- a prompt of PT tokens through wkv_prefill (fp16 cache), then one decode step */
+    {
+#define PT 37
+        const size_t np = (size_t)(PT + 1) * UNITS * D;
+        uint16_t *pq = malloc(np * 2), *pk = malloc(np * 2), *pv = malloc(np * 2), *po = malloc(np * 2);
+        uint16_t chalf[D];
+        for (int c = 0; c < D; ++c) chalf[c] = half_of_64th((int)(lcg(&seed) * 64.0f));
+        for (size_t i = 0; i < np; ++i) {
+            pq[i] = half_of_64th((int)(lcg(&seed) * 64.0f));
+            pk[i] = half_of_64th((int)(lcg(&seed) * 64.0f));
+            pv[i] = chalf[i % D];
+        }
+        uint16_t *gq, *gk, *gv, *go;
+        HIP(hipMalloc((void**)&gq, np * 2)); HIP(hipMalloc((void**)&gk, np * 2));
+        HIP(hipMalloc((void**)&gv, np * 2)); HIP(hipMalloc((void**)&go, np * 2));
+        HIP(hipMemcpy(gq, pq, np * 2, hipMemcpyHostToDevice));
+        HIP(hipMemcpy(gk, pk, np * 2, hipMemcpyHostToDevice));
+        HIP(hipMemcpy(gv, pv, np * 2, hipMemcpyHostToDevice));
+        HIP(hipMemset(go, 0, np * 2));
+        WKV(wkv_create(&h, B, H, D, M, R, WKV_FP16));
+        CHECK(wkv_prefill(h, gq, gk, gv, go, 0, NULL) == WKV_EINVAL);
+        WKV(wkv_prefill(h, gq, gk, gv, go, PT, NULL));
+        CHECK(wkv_prefill(h, gq, gk, gv, go, PT, NULL) == WKV_EINVAL);       /* the cache is no longer empty */
+        const size_t step = (size_t)UNITS * D;
+        WKV(wkv_step(h, gq + PT * step, gk + PT * step, gv + PT * step, go + PT * step, NULL));
+        HIP(hipDeviceSynchronize());
+        HIP(hipMemcpy(po, go, np * 2, hipMemcpyDeviceToHost));
+        for (size_t i = 0; i < np; ++i) {
+            const float want = half_value(chalf[i % D]);
+            CHECK(fabsf(half_value(po[i]) - want) <= 2e-3f * fabsf(want) + 1e-6f);
+        }
+        WKV(wkv_state(h, WKV_STEP, &tokens, sizeof tokens));
+        WKV(wkv_state(h, WKV_LEN, &len, sizeof len));
+        CHECK(tokens == PT + 1 && len == M);
+        WKV(wkv_state(h, WKV_POS, pos, sizeof pos));
+        WKV(wkv_state(h, WKV_NMERGED, nm, sizeof nm));
+        for (int u = 0; u < UNITS; ++u) {
+            int total = 0;
+            for (int l = 0; l < M; ++l) {
+                if (l) CHECK(pos[u * M + l] > pos[u * M + l - 1]);
+                total += nm[u * M + l];
+            }
+            CHECK(pos[u * M + M - 1] == PT && total == PT + 1);
+        }
+        WKV(wkv_destroy(h));
+        HIP(hipFree(gq)); HIP(hipFree(gk)); HIP(hipFree(gv)); HIP(hipFree(go));
+        free(pq); free(pk); free(pv); free(po);
+    }
     printf("c_abi ok\n");
     return 0;
 }
