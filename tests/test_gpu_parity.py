@@ -82,6 +82,17 @@ def test_budgets_that_are_whole_chunks(dtype, d, threads):
         _run(cfg, threads=threads, n_sink=sink)
 
 
+@pytest.mark.parametrize("threads", [256, 512])
+@pytest.mark.parametrize("dtype,d", [("fp16", 128), ("bf16", 64), ("fp32", 64)])
+def test_budgets_just_above_a_chunk_take_the_shallower_chunk(dtype, d, threads):
+    """With m + 1 a little above a multiple of the deep chunk (8 rows per 16-lane group) the host
+    launches the variant with 4 rows per group, which pads less; m = 130, 260, 520 do that at one of
+    the two workgroup sizes, m = 250 does not."""
+    for m, R in ((130, 2), (260, 1), (520, 7), (250, 3)):
+        cfg = synth.StreamConfig(f"half{m}", 7450 + m, 1, 3, d, dtype, m + 60, m, R)
+        _run(cfg, threads=threads)
+
+
 # ---- the sliced kernel (several workgroups per unit, for caches with few units)
 @pytest.mark.parametrize("split", [2, 4, 8, 16])
 def test_sliced_units_small_shapes(split):
