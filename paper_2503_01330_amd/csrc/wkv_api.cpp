@@ -75,11 +75,13 @@ int validate(const wkv_options& o, int* threads, int* split)
         return lds <= LDS_LIMIT && o.budget + 1 <= wkv_step_max_entries(n);
     };
     if (th == 0) {
-        // few units: large workgroups so that one unit's rows are spread over many waves; many
+        // up to one unit per compute unit (256): large workgroups, so that one unit's rows are spread
+        // over many waves (a compute unit holds only one workgroup of 1024 threads: 384 units take
+        // 26.3 us with 1024 threads, 23.4 with 512); more
         // units: 512 threads (measured 2-9 % ahead of 256 for rows of 256 bytes at 1024-8192
         // units), except for 128-byte rows, where 256 threads are 20 % ahead; slices: 512
         const int row_bytes = o.head_dim * dtype_bytes(o.dtype);
-        th = sp > 1 ? 512 : units >= 1024 ? (row_bytes < 256 ? 256 : 512) : units >= 512 ? 512 : 1024;
+        th = sp > 1 ? 512 : units >= 1024 ? (row_bytes < 256 ? 256 : 512) : units > 256 ? 512 : 1024;
         while (th < 1024 && !fits(th)) th *= 2;
     }
     if (th != 256 && th != 512 && th != 1024) return fail(WKV_EINVAL, "threads must be 256, 512 or 1024");
