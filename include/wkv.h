@@ -108,6 +108,10 @@ int wkv_create_ex(wkv_handle** h, const wkv_options* opt);
  * the handle.  After the step completes the cache holds min(tokens, budget)
  * slots per unit.  Arguments are checked on the host before anything is
  * launched; on error nothing is enqueued and the cache is unchanged.
+ * Steps of one handle must be enqueued in token order on streams that order
+ * them (normally one stream).  The token index lives in the handle, on the
+ * host, and travels as a kernel argument: a step recorded into a HIP graph
+ * would replay that one index, so replaying recorded steps is not supported.
  */
 int wkv_step(wkv_handle* h, const void* q, const void* k_new, const void* v_new,
              void* out, void* stream);
