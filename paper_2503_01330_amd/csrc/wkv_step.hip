@@ -71,7 +71,12 @@ namespace {
 // SEP: the incoming token is attended outside the chunked streaming (by the wave whose group
 // would have held it).  Chosen by the host when the budget is a multiple of the chunk, where
 // entry m would otherwise cost every wave one more, almost empty, chunk of K and of V.
-template <class TT, int D, int U, int MAXT, bool SEP>
+//
+// DED: wave 0 streams K like every other wave but takes no V rows: the V phase is spread over the
+// other waves (NG - 4 groups), and wave 0 has only the bookkeeping between the two barriers.
+// Without it wave 0 does the bookkeeping (~2.6 us for 411 entries) and then its share of V, and
+// the other 15 waves wait ~1.7 us for it at the second barrier.  Used with 1024-thread workgroups.
+template <class TT, int D, int U, int MAXT, bool SEP, bool DED>
 __global__ __launch_bounds__(MAXT)
 void wkv_step_kernel(WkvCache c, const void* __restrict__ q_, const void* __restrict__ k_,
                      const void* __restrict__ v_, void* __restrict__ out_, int t)
@@ -96,6 +101,14 @@ void wkv_step_kernel(WkvCache c, const void* __restrict__ q_, const void* __rest
     const int nchunks = (Ls > CH) ? (Ls + CH - 1) / CH : 1;
     const int g_in = Lc & (NG - 1);                        // SEP: the group that owns the incoming entry
     const bool own_in = SEP && wid == (g_in >> 2);         //      and its wave
+    // V phase: which groups stream V rows
+    const int NGv = DED ? NG - 4 : NG;                     // groups that take V rows
+    const int vgid = DED ? gid - 4 : gid;                  // (negative in wave 0 with DED: unused)
+    const bool has_v = !DED || wid != 0;
+    const int CHv = NGv * U;
+    const int nchv = (Ls > CHv) ? (Ls + CHv - 1) / CHv : 1;
+    const int gv_in = DED ? ((g_in >= 4) ? g_in - 4 : 0) : g_in;   // SEP: the V group that adds the incoming value
+    const bool own_in_v = SEP && has_v && (vgid >> 2) == (gv_in >> 2);
 
     // ---- LDS carve-up
     extern __shared__ double lds[];
@@ -150,17 +163,20 @@ void wkv_step_kernel(WkvCache c, const void* __restrict__ q_, const void* __rest
 
     // ---- row requests.  Chunk ch of a matrix: entries gid + ch*CH + uu*NG, uu < U.
     uint32_t kw[U][NW32], vw[U][NW32];
-    auto request = [&](uint32_t (&dst)[U][NW32], const char* cached, const char* incoming, int ch) {
-        const int base = ch * CH + gid;
+    auto request_rows = [&](uint32_t (&dst)[U][NW32], const char* cached, const char* incoming, int base, int stride) {
         const int dup = (base < Ls) ? base : 0;            // where out-of-range groups point (harmless duplicate)
 #pragma unroll
         for (int uu = 0; uu < U; ++uu) {
-            int i = base + uu * NG;
+            int i = base + uu * stride;
             if (i >= Ls) i = dup;
             const char* rp = (!SEP && i == Lc) ? incoming : cached + (size_t)i * ROWB;
             load_words<NW32>(rp + sub * LANEB, dst[uu]);
         }
     };
+    auto request = [&](uint32_t (&dst)[U][NW32], const char* cached, const char* incoming, int ch) {
+        request_rows(dst, cached, incoming, ch * CH + gid, NG);
+    };
+    auto request_v = [&](int ch) { request_rows(vw, Vc, vu, ch * CHv + vgid, NGv); };
 
     request(kw, Kc, ku, 0);
 
@@ -208,7 +224,17 @@ void wkv_step_kernel(WkvCache c, const void* __restrict__ q_, const void* __rest
     logits(nchunks - 1);
     [[maybe_unused]] uint32_t vin[NW32];                    // SEP: the incoming value in row layout
     if constexpr (SEP) load_words<NW32>(vu + sub * LANEB, vin);
-    request(vw, Vc, vu, 0);                                // this wave's K is done: its V rows may queue now
+    // stage what the bookkeeping needs (these loads are older than the K rows: they have arrived): score sums, token indices, and token order as a linked
+    // list (nl[i] = entry that follows entry i; the newest cached token is followed by the
+    // incoming one, entry Lc)
+#pragma unroll
+    for (int k = 0; k < MAXPT; ++k) {
+        const int i = tid + k * NT;
+        if (i < Lc) { al[i] = a_reg[k]; pl[i] = pos_reg[k]; nl[i] = (nxt_reg[k] < 0) ? Lc : nxt_reg[k]; }
+        else if (i == Lc) { al[i] = 0.0; pl[i] = t; nl[i] = -1; }      // a = [a, 0]
+    }
+    if (tid == 0) { bk_i[0] = -1; bk_i[1] = -1; bk_i[2] = -1; bk_i[3] = 0; bk_i[4] = 0; }
+    if (has_v) request_v(0);                               // this wave's K is done: its V rows may queue now
     WKV_MARK(1);
 
     // mx is uniform within each 16-lane row: combine the four rows of the wave
@@ -225,16 +251,6 @@ void wkv_step_kernel(WkvCache c, const void* __restrict__ q_, const void* __rest
         psum = wave_sum(psum);
         if (lane == 0) { wmax[wid] = mx; wsum[wid] = psum; }
     }
-    // stage what the bookkeeping needs: score sums, token indices, and token order as a linked
-    // list (nl[i] = entry that follows entry i; the newest cached token is followed by the
-    // incoming one, entry Lc)
-#pragma unroll
-    for (int k = 0; k < MAXPT; ++k) {
-        const int i = tid + k * NT;
-        if (i < Lc) { al[i] = a_reg[k]; pl[i] = pos_reg[k]; nl[i] = (nxt_reg[k] < 0) ? Lc : nxt_reg[k]; }
-        else if (i == Lc) { al[i] = 0.0; pl[i] = t; nl[i] = -1; }      // a = [a, 0]
-    }
-    if (tid == 0) { bk_i[0] = -1; bk_i[1] = -1; bk_i[2] = -1; bk_i[3] = 0; bk_i[4] = 0; }
     WKV_MARK(2);
     // barrier 1: logits, exponentials, score sums, token indices and links are staged.  Only
     // LDS traffic has to be complete; the V rows requested above stay in flight.
@@ -293,10 +309,10 @@ void wkv_step_kernel(WkvCache c, const void* __restrict__ q_, const void* __rest
 #pragma unroll
     for (int e = 0; e < EPL; ++e) acc[e] = (S)0;
     auto weighted_sum = [&](int ch) {
-        const int base = ch * CH + gid;
+        const int base = ch * CHv + vgid;
 #pragma unroll
         for (int uu = 0; uu < U; ++uu) {
-            const int i = base + uu * NG;
+            const int i = base + uu * NGv;
             const S p = (i < Ls) ? soft_exp((S)(sl[(i < Ls) ? i : 0] - Mx)) : (S)0;
             float vx[EPL];
             decode<TT, EPL, NW32>(vw[uu], vx);
@@ -305,18 +321,20 @@ void wkv_step_kernel(WkvCache c, const void* __restrict__ q_, const void* __rest
             for (int e = 0; e < EPL; ++e) acc[e] += p * (S)vx[e];
         }
     };
-    if constexpr (SEP) {
-        if (own_in) {                                      // the incoming token, counted by its group only
-            const S p = (gid == g_in) ? soft_exp((S)(sl[Lc] - Mx)) : (S)0;
-            float vx[EPL];
-            decode<TT, EPL, NW32>(vin, vx);
-            l_run += p;
+    if (has_v) {
+        weighted_sum(0);                                   // the chunk requested during the K phase
+        if constexpr (SEP) {
+            if (own_in_v) {                                // the incoming token, counted by one group only
+                const S p = (vgid == gv_in) ? soft_exp((S)(sl[Lc] - Mx)) : (S)0;
+                float vx[EPL];
+                decode<TT, EPL, NW32>(vin, vx);
+                l_run += p;
 #pragma unroll
-            for (int e = 0; e < EPL; ++e) acc[e] += p * (S)vx[e];
+                for (int e = 0; e < EPL; ++e) acc[e] += p * (S)vx[e];
+            }
         }
+        for (int ch = 1; ch < nchv; ++ch) { request_v(ch); weighted_sum(ch); }
     }
-    weighted_sum(0);                                       // the chunk requested during the K phase
-    for (int ch = 1; ch < nchunks; ++ch) { request(vw, Vc, vu, ch); weighted_sum(ch); }
     {
         S l_w = l_run;
         S acc_w[EPL];
@@ -355,11 +373,11 @@ void wkv_step_kernel(WkvCache c, const void* __restrict__ q_, const void* __rest
         // the merge needs the V rows of the victim and of its right neighbour.  The rows of the
         // last chunk are still in registers: their holders leave a copy in LDS.  (A row of an
         // earlier chunk is fetched again by wave 0 below; with one chunk that never happens.)
-        if (compress && c.merge_mode == 0) {
-            const int base = (nchunks - 1) * CH + gid;
+        if (compress && c.merge_mode == 0 && has_v) {
+            const int base = (nchv - 1) * CHv + vgid;
 #pragma unroll
             for (int uu = 0; uu < U; ++uu) {
-                const int i = base + uu * NG;
+                const int i = base + uu * NGv;
                 if (i < Ls && (i == j || i == r)) {
                     uint32_t* dstw = (i == j) ? vj_raw : vr_raw;
 #pragma unroll
@@ -412,7 +430,7 @@ void wkv_step_kernel(WkvCache c, const void* __restrict__ q_, const void* __rest
             if (col < D) {
                 if (merge) {
                     // V[r] <- (abar_j V[j] + abar_r V[r]) / (abar_j + abar_r)     (Algorithm 1, Section IV)
-                    const int first_held = (nchunks - 1) * CH;     // entries >= this were staged in LDS
+                    const int first_held = (nchv - 1) * CHv;       // entries >= this were staged in LDS
                     const double vj = (double)((j >= first_held) ? load_elem<TT>(vj_raw, col)
                                                                  : load_elem<TT>(Vc + (size_t)j * ROWB, col));
                     const double vr = (double)((SEP && r == Lc) ? bits_elem<TT>(vnew_b[e])
@@ -457,14 +475,29 @@ inline int row_slots(int m, int ch, bool* sep)
     return (ls + ch - 1) / ch * ch;
 }
 
+// Wave 0 is kept free of V rows (DED at the kernel) in the 1024-thread workgroups always; in
+// the smaller ones when the launch is not large enough for many workgroups per compute unit to
+// overlap each other's serial stretches.  Measured (512 threads, d = 128, 16-bit): 384 units
+// x 410 slots 23.6 -> 21.9 us, 1024 x 520 47.2 -> 45.3 (0.79 of peak), 2048 x 512 102.7 -> 103.4.
+inline bool dedicated_wave(const WkvCache& c, int threads, size_t row_bytes)
+{
+    return threads > 512 || (size_t)c.units * (size_t)(c.m + 1) * row_bytes * 2 <= (size_t)400 << 20;
+}
+
 template <class TT, int D, int U, int MAXT>
 hipError_t prepare_u(size_t lds)
 {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&wkv_step_kernel<TT, D, U, MAXT, false>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    if (e != hipSuccess) return e;
-    return hipFuncSetAttribute(reinterpret_cast<const void*>(&wkv_step_kernel<TT, D, U, MAXT, true>),
-                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    const void* ks[] = {
+        reinterpret_cast<const void*>(&wkv_step_kernel<TT, D, U, MAXT, false, true>),
+        reinterpret_cast<const void*>(&wkv_step_kernel<TT, D, U, MAXT, true, true>),
+        reinterpret_cast<const void*>(&wkv_step_kernel<TT, D, U, MAXT, false, (MAXT > 512)>),
+        reinterpret_cast<const void*>(&wkv_step_kernel<TT, D, U, MAXT, true, (MAXT > 512)>),
+    };
+    for (const void* k : ks) {
+        hipError_t e = hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
 }
 
 template <class TT, int D, int MAXT>
@@ -478,17 +511,28 @@ hipError_t prepare(size_t lds)
     return e;
 }
 
+template <class TT, int D, int U, int MAXT, bool DED>
+hipError_t launch_ud(const WkvCache& c, int threads, size_t lds, bool sep, const void* q, const void* k,
+                     const void* v, void* out, int t, hipStream_t stream)
+{
+    if (sep)
+        hipLaunchKernelGGL((wkv_step_kernel<TT, D, U, MAXT, true, DED>), dim3(c.units), dim3(threads), lds,
+                           stream, c, q, k, v, out, t);
+    else
+        hipLaunchKernelGGL((wkv_step_kernel<TT, D, U, MAXT, false, DED>), dim3(c.units), dim3(threads), lds,
+                           stream, c, q, k, v, out, t);
+    return hipGetLastError();
+}
+
 template <class TT, int D, int U, int MAXT>
 hipError_t launch_u(const WkvCache& c, int threads, size_t lds, bool sep, const void* q, const void* k,
                     const void* v, void* out, int t, hipStream_t stream)
 {
-    if (sep)
-        hipLaunchKernelGGL((wkv_step_kernel<TT, D, U, MAXT, true>), dim3(c.units), dim3(threads), lds,
-                           stream, c, q, k, v, out, t);
-    else
-        hipLaunchKernelGGL((wkv_step_kernel<TT, D, U, MAXT, false>), dim3(c.units), dim3(threads), lds,
-                           stream, c, q, k, v, out, t);
-    return hipGetLastError();
+    if constexpr (MAXT <= 512) {
+        if (!dedicated_wave(c, threads, (size_t)D * TT::BYTES))
+            return launch_ud<TT, D, U, MAXT, false>(c, threads, lds, sep, q, k, v, out, t, stream);
+    }
+    return launch_ud<TT, D, U, MAXT, true>(c, threads, lds, sep, q, k, v, out, t, stream);
 }
 
 template <class TT, int D, int MAXT>
