@@ -168,6 +168,19 @@ template <int CTRL> __device__ __forceinline__ void best_step(Best& b) {
 }
 
 __device__ __forceinline__ Best wave_argmin(Best b) {
+    // Fast path: the smallest score by a plain fp64 minimum (three instructions per exchange
+    // instead of a compare-and-select of the whole record); if exactly one lane holds it, that
+    // lane's record is the answer.  Scores are never NaN here.  Ties take the full reduction.
+    {
+        double mn = b.s;
+        mn = fmin(mn, dpp<0xB1>(mn)); mn = fmin(mn, dpp<0x4E>(mn)); mn = fmin(mn, dpp<0x141>(mn)); mn = fmin(mn, dpp<0x140>(mn));
+        mn = fmin(fmin(readlane_f64(mn, 0), readlane_f64(mn, 16)), fmin(readlane_f64(mn, 32), readlane_f64(mn, 48)));
+        const unsigned long long holders = __ballot(b.s == mn);
+        if (__popcll(holders) == 1) {
+            const int l = __ffsll((long long)holders) - 1;
+            return { mn, __builtin_amdgcn_readlane(b.pos, l), __builtin_amdgcn_readlane(b.phys, l) };
+        }
+    }
     best_step<0xB1>(b); best_step<0x4E>(b); best_step<0x141>(b); best_step<0x140>(b);
     Best r = { readlane_f64(b.s, 0), __builtin_amdgcn_readlane(b.pos, 0), __builtin_amdgcn_readlane(b.phys, 0) };
 #pragma unroll

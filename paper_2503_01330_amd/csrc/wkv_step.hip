@@ -37,6 +37,8 @@
 // per-wave results are combined by one DPP row reduction per wave, and the two
 // V rows of the merge are taken from the registers they were streamed into.
 #include "wkv_internal.h"
+#include <type_traits>
+
 #include "wkv_device.h"
 
 // Phase markers for an out-of-tree timing harness; they compile to nothing in the library.
@@ -63,10 +65,10 @@ namespace {
 //      bookkeeping of Algorithm 1 in fp64 (softmax denominator, a += A_t, abar = a/n,
 //      arg-min, right neighbour) from LDS while V arrives and the waves accumulate
 //      exp(logit - max) . V;
-//   4. barrier 2: victim and neighbour are known.  The groups that hold their V rows (still
-//      in registers) stage them; every thread writes back the score sum and link of the
-//      entry it owns; barrier 3; o_t, the merged V row and the incoming token's rows are
-//      written.
+//   4. barrier 2: victim and neighbour are known.  Wave 0, which requested the two V rows of
+//      the merge as soon as it knew them, writes the merged row and the incoming token's rows;
+//      every thread writes back the score sum and link of the entry it owns; the last waves
+//      write o_t; barrier 3; the log entry.
 //
 // SEP: the incoming token is attended outside the chunked streaming (by the wave whose group
 // would have held it).  Chosen by the host when the budget is a multiple of the chunk, where
@@ -124,8 +126,6 @@ void wkv_step_kernel(WkvCache c, const void* __restrict__ q_, const void* __rest
     int*      pl     = reinterpret_cast<int*>(plw + 16);   // [m+1] token index of every entry
     int*      nl     = pl + m + 1;                         // [m+1] entry that follows in token order
     int*      bk_i   = nl + m + 1;                         // [16] bookkeeping result: victim, neighbour, token, rank
-    uint32_t* vj_raw = reinterpret_cast<uint32_t*>(bk_i + 16);   // [ROWB/4] the victim's V row
-    uint32_t* vr_raw = vj_raw + ROWB / 4;                  // [ROWB/4] its right neighbour's V row
 
     char*       Kc = reinterpret_cast<char*>(c.K) + (size_t)u * m * ROWB;
     char*       Vc = reinterpret_cast<char*>(c.V) + (size_t)u * m * ROWB;
@@ -259,6 +259,7 @@ void wkv_step_kernel(WkvCache c, const void* __restrict__ q_, const void* __rest
     WKV_MARK(3);
     const double Mx = combine_max(wmax, NW, lane);
 
+    uint32_t vj_b[EPW] = {}, vr_b[EPW] = {};               // wave 0: the two V rows of the merge (raw)
     if (wid == 0) {
         // ---- wave 0: the bookkeeping of Algorithm 1, in fp64, from LDS, while V arrives
         {   // softmax denominator from the per-wave partial sums; fw[w] rescales wave w's exponentials
@@ -269,18 +270,57 @@ void wkv_step_kernel(WkvCache c, const void* __restrict__ q_, const void* __rest
         }
         Best best = { INFINITY, NONE_POS, -1 };
         int nonfinite = 0;
-        for (int i = lane; i < L; i += 64) {
-            const double p = el[i] * fw[(i & (NG - 1)) >> 2];        // A_t[i]
-            const double ai = al[i] + p;                             // a = [a, 0] + A_t
-            al[i] = ai;
-            if (compress) {
-                const int pi = pl[i];
-                const double ni = (double)(t - pi + 1);              // n: steps this token has been attended
-                double score = (c.score_mode == 0) ? ai / ni : (c.score_mode == 1) ? ai : p;
-                if (!(score == score) || score == INFINITY) { score = INFINITY; nonfinite = 1; }
-                if (pi <= t - c.R && pi >= c.n_sink && better(score, pi, best)) best = { score, pi, i };
+        // BK entries per lane at a time, in straight-line code: their LDS reads are in flight
+        // together and their divisions interleave (one entry at a time, each trip is a chain of
+        // two LDS round trips and a 14-instruction fp64 division that nothing overlaps)
+        constexpr int BK = 4;
+        const int newest_cand = t - c.R, n_sink = c.n_sink;
+        auto batches = [&](auto mode_c) {                            // the scoring rule as a constant: no branch per entry
+            constexpr int MODE = decltype(mode_c)::value;
+            for (int b0 = 0; b0 < L; b0 += 64 * BK) {
+                double e[BK], a[BK], f[BK];
+                int pi[BK];
+#pragma unroll
+                for (int k = 0; k < BK; ++k) {
+                    const int i = b0 + 64 * k + lane;
+                    const int ic = (i < L) ? i : L - 1;              // past the end: a duplicate, never stored or ranked
+                    e[k] = el[ic]; a[k] = al[ic]; pi[k] = pl[ic];
+                    f[k] = fw[(ic & (NG - 1)) >> 2];
+                }
+                double p[BK], ai[BK];
+#pragma unroll
+                for (int k = 0; k < BK; ++k) {
+                    const int i = b0 + 64 * k + lane;
+                    p[k] = e[k] * f[k];                              // A_t[i]
+                    ai[k] = a[k] + p[k];                             // a = [a, 0] + A_t
+                    if (i < L) al[i] = ai[k];
+                }
+                if (compress) {
+                    double score[BK];
+#pragma unroll
+                    for (int k = 0; k < BK; ++k) {
+                        double sc;
+                        if constexpr (MODE == 0) sc = ai[k] / (double)(t - pi[k] + 1);   // abar = a / n, n = steps attended
+                        else if constexpr (MODE == 1) sc = ai[k];
+                        else sc = p[k];
+                        const bool bad = !(sc == sc) | (sc == INFINITY);
+                        score[k] = bad ? INFINITY : sc;
+                        nonfinite |= (bad & (b0 + 64 * k + lane < L)) ? 1 : 0;
+                    }
+#pragma unroll
+                    for (int k = 0; k < BK; ++k) {                   // selects, no short-circuit: stays one basic block
+                        const bool cand = (b0 + 64 * k + lane < L) & (pi[k] <= newest_cand) & (pi[k] >= n_sink);
+                        const bool take = cand & ((score[k] < best.s) | ((score[k] == best.s) & (pi[k] < best.pos)));
+                        best.s = take ? score[k] : best.s;
+                        best.pos = take ? pi[k] : best.pos;
+                        best.phys = take ? b0 + 64 * k + lane : best.phys;
+                    }
+                }
             }
-        }
+        };
+        if (c.score_mode == 0) batches(std::integral_constant<int, 0>{});
+        else if (c.score_mode == 1) batches(std::integral_constant<int, 1>{});
+        else batches(std::integral_constant<int, 2>{});
         if (nonfinite) atomicAdd(&c.status[1], 1);
         if (compress) {
             best = wave_argmin(best);
@@ -289,6 +329,18 @@ void wkv_step_kernel(WkvCache c, const void* __restrict__ q_, const void* __rest
             // a right neighbour.  Should the cache ever be inconsistent, touch nothing and flag it.
             bool sane = j >= 0 && j < Lc;
             if (sane) { r = nl[j]; sane = r >= 0 && r <= Lc && r != j; }
+            // The merge needs the V rows of the victim and of its right neighbour: requested here,
+            // used after the second barrier, so that their round trip overlaps the V phase.
+            if (sane && c.merge_mode == 0) {
+                const char* rj = Vc + (size_t)j * ROWB;
+                const char* rr = (r == Lc) ? vu : Vc + (size_t)r * ROWB;
+#pragma unroll
+                for (int e = 0; e < EPW; ++e) {
+                    const int col = (lane + 64 * e < D) ? lane + 64 * e : 0;
+                    vj_b[e] = load_bits<TT>(rj, col);
+                    vr_b[e] = load_bits<TT>(rr, col);
+                }
+            }
             if (lane == 0) {
                 if (sane) {
                     bk_i[0] = j; bk_i[1] = r; bk_i[2] = best.pos;
@@ -335,7 +387,7 @@ void wkv_step_kernel(WkvCache c, const void* __restrict__ q_, const void* __rest
         }
         for (int ch = 1; ch < nchv; ++ch) { request_v(ch); weighted_sum(ch); }
     }
-    {
+    if (has_v) {                                           // a wave without V rows has nothing to add
         S l_w = l_run;
         S acc_w[EPL];
 #pragma unroll
@@ -363,28 +415,43 @@ void wkv_step_kernel(WkvCache c, const void* __restrict__ q_, const void* __rest
     if (tid >= NT - D) {  // o_t = A_t^T V_t   (Section III-A); the last waves, wave 0 has the row write-back
         const int col = tid - (NT - D);
         S num = (S)0, den = (S)0;
-        for (int w = 0; w < NW; ++w) { num += part[w * D + col]; den += plw[w]; }
+        for (int w = DED ? 1 : 0; w < NW; ++w) { num += part[w * D + col]; den += plw[w]; }
         const S o = num / den;
         if constexpr (TT::BYTES == 4) reinterpret_cast<float*>(out_)[(size_t)u * D + col] = (float)o;
         else store_elem<TT>(out_, (size_t)u * D + col, (float)o);
     }
 
-    if (sane) {
-        // the merge needs the V rows of the victim and of its right neighbour.  The rows of the
-        // last chunk are still in registers: their holders leave a copy in LDS.  (A row of an
-        // earlier chunk is fetched again by wave 0 below; with one chunk that never happens.)
-        if (compress && c.merge_mode == 0 && has_v) {
-            const int base = (nchv - 1) * CHv + vgid;
+    if (wid == 0 && sane) {
+        // ---- write-back of the rows: merged value, then the incoming token into its slot
+        const bool merge = compress && c.merge_mode == 0;
+        const double sj = bk_d[0], sr = bk_d[1];
+        const double den = sj + sr;
+        const bool zero_den = !(den > 0.0);
 #pragma unroll
-            for (int uu = 0; uu < U; ++uu) {
-                const int i = base + uu * NGv;
-                if (i < Ls && (i == j || i == r)) {
-                    uint32_t* dstw = (i == j) ? vj_raw : vr_raw;
-#pragma unroll
-                    for (int w = 0; w < NW32; ++w) dstw[sub * NW32 + w] = vw[uu][w];
+        for (int e = 0; e < EPW; ++e) {
+            const int col = lane + 64 * e;
+            if (col < D) {
+                if (merge) {
+                    // V[r] <- (abar_j V[j] + abar_r V[r]) / (abar_j + abar_r)     (Algorithm 1, Section IV)
+                    const double vj = (double)bits_elem<TT>(vj_b[e]);
+                    const double vr = (double)bits_elem<TT>(vr_b[e]);
+                    const double x = zero_den ? 0.5 * vj + 0.5 * vr : (sj * vj + sr * vr) / den;
+                    if (r == Lc) {
+                        store_elem_f64<TT>(Vc + (size_t)dest * ROWB, col, x);   // folded straight into the new token
+                    } else {
+                        store_elem_f64<TT>(Vc + (size_t)r * ROWB, col, x);
+                        store_bits<TT>(Vc + (size_t)dest * ROWB, col, vnew_b[e]);
+                    }
+                } else {
+                    store_bits<TT>(Vc + (size_t)dest * ROWB, col, vnew_b[e]);
                 }
+                store_bits<TT>(Kc + (size_t)dest * ROWB, col, knew_b[e]);
             }
         }
+        if (lane == 0 && merge && zero_den) atomicAdd(&c.status[0], 1);
+    }
+
+    if (sane) {
         // score sums, token indices and links back to memory: every entry's owner stores its
         // own, the victim's owner stores nothing, the incoming token's owner stores into the
         // destination.  Links: the newest cached token is now followed by the incoming one
@@ -415,42 +482,9 @@ void wkv_step_kernel(WkvCache c, const void* __restrict__ q_, const void* __rest
         }
     }
     WKV_MARK(6);
-    WKV_LDS_BARRIER();   // barrier 3: the two rows and the rank are staged (global stores keep flying)
+    WKV_LDS_BARRIER();   // barrier 3: the victim's rank is complete (global stores keep flying)
 #undef WKV_LDS_BARRIER
 
-    if (wid == 0 && sane) {
-        // ---- write-back of the rows: merged value, then the incoming token into its slot
-        const bool merge = compress && c.merge_mode == 0;
-        const double sj = bk_d[0], sr = bk_d[1];
-        const double den = sj + sr;
-        const bool zero_den = !(den > 0.0);
-#pragma unroll
-        for (int e = 0; e < EPW; ++e) {
-            const int col = lane + 64 * e;
-            if (col < D) {
-                if (merge) {
-                    // V[r] <- (abar_j V[j] + abar_r V[r]) / (abar_j + abar_r)     (Algorithm 1, Section IV)
-                    const int first_held = (nchv - 1) * CHv;       // entries >= this were staged in LDS
-                    const double vj = (double)((j >= first_held) ? load_elem<TT>(vj_raw, col)
-                                                                 : load_elem<TT>(Vc + (size_t)j * ROWB, col));
-                    const double vr = (double)((SEP && r == Lc) ? bits_elem<TT>(vnew_b[e])
-                                               : (r >= first_held) ? load_elem<TT>(vr_raw, col)
-                                                                   : load_elem<TT>(Vc + (size_t)r * ROWB, col));
-                    const double x = zero_den ? 0.5 * vj + 0.5 * vr : (sj * vj + sr * vr) / den;
-                    if (r == Lc) {
-                        store_elem_f64<TT>(Vc + (size_t)dest * ROWB, col, x);   // folded straight into the new token
-                    } else {
-                        store_elem_f64<TT>(Vc + (size_t)r * ROWB, col, x);
-                        store_bits<TT>(Vc + (size_t)dest * ROWB, col, vnew_b[e]);
-                    }
-                } else {
-                    store_bits<TT>(Vc + (size_t)dest * ROWB, col, vnew_b[e]);
-                }
-                store_bits<TT>(Kc + (size_t)dest * ROWB, col, knew_b[e]);
-            }
-        }
-        if (lane == 0 && merge && zero_den) atomicAdd(&c.status[0], 1);
-    }
     if (tid == 0) {
         const size_t row = (size_t)(t % c.log_cap) * c.units + u;
         c.log_pos[row] = (compress && sane) ? pj : -1;
@@ -558,8 +592,7 @@ size_t wkv_step_lds_bytes(int m, int dtype, int head_dim, int threads)
 {
     const size_t s = (dtype == 0) ? 8 : 4;     // sizeof(soft_t)
     const size_t nw = (size_t)threads / 64;
-    const size_t rowb = (size_t)head_dim * ((dtype == 0) ? 4 : 2);
-    return ((size_t)m + 1) * 32 + 64 * 8 + (nw * (size_t)head_dim + 16) * s + 16 * 4 + 2 * rowb;
+    return ((size_t)m + 1) * 32 + 64 * 8 + (nw * (size_t)head_dim + 16) * s + 16 * 4;
 }
 
 int wkv_step_max_entries(int threads) { return MAXPT * threads; }
