@@ -53,18 +53,31 @@ template <class TT> __device__ __forceinline__ float frag_elem(const uint32_t* w
     }
 }
 
+// Workgroups are dealt to the chip's eight partitions (each with its own L2) round-robin by index.
+// All workgroups of a unit re-read that unit's 1-2 MB of Q, K and V, so a unit is given to ONE
+// partition: workgroup b belongs to partition b % 8, and there to unit 8 * ((b / 8) / groups) + b % 8.
+// (With units dealt across the partitions instead, every L2 sees the ~10 units in flight at once,
+// more than it holds, and the operands come from the memory-side cache.)
+constexpr int XCDS = 8;
+__device__ __forceinline__ int xcd_unit(unsigned b, int groups) { return (int)((b >> 3) / groups) * XCDS + (int)(b & 7); }
+inline int xcd_grid(int units, int groups) { return (units + XCDS - 1) / XCDS * XCDS * groups; }
+
 __device__ __forceinline__ double xor_max(double v, int mask) { return fmax(v, __shfl_xor(v, mask)); }
 
 // S^T tile: rows = 16 keys, columns = 16 queries; register r of lane (g, x) = key g + 4r, query x.
 // Both operands are the exact storage values; the softmax scale is applied to the four results.
 template <class TT, int D>
 __device__ __forceinline__ double4_t logits_tile(const uint32_t (&kfrag)[D / 8], const double (&qd)[D / 4]) {
-    double4_t s = {0.0, 0.0, 0.0, 0.0};
+    // two accumulators: an MFMA that continues the chain of the one before it waits for that
+    // one's result; alternating chains keeps the matrix unit issuing back to back
+    double4_t s0 = {0.0, 0.0, 0.0, 0.0}, s1 = {0.0, 0.0, 0.0, 0.0};
 #pragma unroll
-    for (int kk = 0; kk < D / 4; ++kk)
-        s = __builtin_amdgcn_mfma_f64_16x16x4f64((double)frag_elem<TT>(kfrag, kk), qd[kk], s, 0, 0, 0);
+    for (int kk = 0; kk < D / 4; kk += 2) {
+        s0 = __builtin_amdgcn_mfma_f64_16x16x4f64((double)frag_elem<TT>(kfrag, kk), qd[kk], s0, 0, 0, 0);
+        s1 = __builtin_amdgcn_mfma_f64_16x16x4f64((double)frag_elem<TT>(kfrag, kk + 1), qd[kk + 1], s1, 0, 0, 0);
+    }
     const double scale = 1.0 / sqrt((double)D);
-    return s * scale;
+    return (s0 + s1) * scale;
 }
 
 // ------------------------------------------------------------------ 1. rows
@@ -81,9 +94,9 @@ void wkv_prefill_rows(const void* __restrict__ q_, const void* __restrict__ k_, 
     const int g = lane >> 4, x = lane & 15;
     const int ntiles = (P + TILE - 1) / TILE;
     const int groups = (ntiles + 3) / 4;
-    const int u = blockIdx.x / groups;
-    const int qt = (groups - 1 - (int)(blockIdx.x % groups)) * 4 + wid;   // long rows are scheduled first
-    if (qt >= ntiles) return;
+    const int u = xcd_unit(blockIdx.x, groups);
+    const int qt = (groups - 1 - (int)((blockIdx.x >> 3) % groups)) * 4 + wid;   // long rows are scheduled first
+    if (u >= units || qt >= ntiles) return;
     const size_t tok = (size_t)units * ROWB;                              // bytes from one token to the next
     const char* qb = reinterpret_cast<const char*>(q_) + (size_t)u * ROWB;
     const char* kb = reinterpret_cast<const char*>(k_) + (size_t)u * ROWB;
@@ -188,9 +201,9 @@ void wkv_prefill_scores(const void* __restrict__ q_, const void* __restrict__ k_
     const int g = lane >> 4, x = lane & 15;
     const int ntiles = (P + TILE - 1) / TILE;
     const int groups = (ntiles + 3) / 4;
-    const int u = blockIdx.x / groups;
-    const int kt = (int)(blockIdx.x % groups) * 4 + wid;                  // low key tiles have the most rows: first
-    if (kt >= ntiles) return;
+    const int u = xcd_unit(blockIdx.x, groups);
+    const int kt = (int)((blockIdx.x >> 3) % groups) * 4 + wid;           // low key tiles have the most rows: first
+    if (u >= units || kt >= ntiles) return;
     const size_t tok = (size_t)units * ROWB;
     const char* qb = reinterpret_cast<const char*>(q_) + (size_t)u * ROWB;
     const char* kb = reinterpret_cast<const char*>(k_) + (size_t)u * ROWB;
@@ -226,7 +239,18 @@ void wkv_prefill_scores(const void* __restrict__ q_, const void* __restrict__ k_
         for (int e = 0; e < CH; ++e) qd[e] = (double)frag_elem<TT>(wnext, e);
         const double l_next = lnext;
         request(min(qt + 2, ntiles - 1));
-        const double4_t s_next = logits_tile<TT, D>(kfrag, qd);           // tile qt + 1 (a repeat on the last round)
+        __builtin_amdgcn_sched_barrier(0);                                 // the requests are issued here, not later
+        double4_t s_next = logits_tile<TT, D>(kfrag, qd);                 // tile qt + 1 (a repeat on the last round)
+        // The fragment just requested may be touched only once this chain has been issued: without
+        // these opaque uses the compiler converts it right behind its request, i.e. every round
+        // waits for the loads it has just issued.
+        {
+            double pin = s_next[0];
+#pragma unroll
+            for (int w = 0; w < CH / 2; ++w) asm volatile("" : "+v"(pin), "+v"(wnext[w]));
+            asm volatile("" : "+v"(pin), "+v"(lnext));
+            s_next[0] = pin;
+        }
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
             const int key = kt * TILE + g + 4 * r;
@@ -493,8 +517,8 @@ hipError_t run(const WkvCache& c, const void* q, const void* k, const void* v, v
                double* lse, double* a, int P, hipStream_t stream)
 {
     const int ntiles = (P + TILE - 1) / TILE, groups = (ntiles + 3) / 4;
-    hipLaunchKernelGGL((wkv_prefill_rows<TT, D>), dim3(c.units * groups), dim3(256), 0, stream, q, k, v, out, lse, P, c.units);
-    hipLaunchKernelGGL((wkv_prefill_scores<TT, D>), dim3(c.units * groups), dim3(256), 0, stream, q, k, lse, a, P, c.units);
+    hipLaunchKernelGGL((wkv_prefill_rows<TT, D>), dim3(xcd_grid(c.units, groups)), dim3(256), 0, stream, q, k, v, out, lse, P, c.units);
+    hipLaunchKernelGGL((wkv_prefill_scores<TT, D>), dim3(xcd_grid(c.units, groups)), dim3(256), 0, stream, q, k, lse, a, P, c.units);
     const size_t lds = wkv_prefill_lds_bytes(P);
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&wkv_prefill_compress<TT, D>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
