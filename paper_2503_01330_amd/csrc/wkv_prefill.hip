@@ -14,8 +14,9 @@
 //      The logits are a dense contraction: v_mfma_f64_16x16x4_f64, fp16/bf16 inputs converted to
 //      fp64 (products and sums then reproduce an fp64 reference to ~1e-16, which is what makes
 //      the later selection reproduce it exactly, as in the decode kernels).  Online softmax in
-//      fp64; P.V in fp32 with v_mfma_f32_16x16x4_f32, fed straight from the registers the
-//      logits arrive in.  Writes o_t and the log-sum-exp of every row.
+//      fp64; P.V with v_mfma_f32_16x16x16_f16 / _bf16 (fp32 accumulation): the weights go in as
+//      hi + lo 16-bit pairs straight from the registers the logits arrive in, the values as the raw
+//      cache words.  Writes o_t and the log-sum-exp of every row.
 //   2. wkv_prefill_scores: the column sums a_i = sum_{t >= i} exp(s_ti - lse_t): one wave per
 //      tile of 16 keys, looping over the query tiles below the diagonal, the same fp64 MFMA
 //      contraction again (recomputing the logits costs less than storing P^2/2 of them);
@@ -28,7 +29,9 @@
 // MFMA operand layouts (one wave; g = lane / 16, x = lane % 16), as measured on gfx950:
 //   both: A operand = A[row x][k = g], B operand = B[k = g][column x];
 //   f64 16x16x4: result register r holds D[row g + 4r][column x];
-//   f32 16x16x4: result register r holds D[row 4g + r][column x].
+//   f32 16x16x4: result register r holds D[row 4g + r][column x];
+//   f32 16x16x16 (16-bit inputs): A operand = A[row x][k = 4g .. 4g+3], B operand = B[k = 4g .. 4g+3][column x],
+//   result as f32 16x16x4.
 // The reduction index of a contraction may be permuted at will as long as A and B agree, so a lane
 // simply takes a contiguous quarter of its row: MFMA step kk uses element g*(D/4) + kk of both.
 #include "wkv_internal.h"
@@ -38,6 +41,10 @@ namespace {
 
 typedef double double4_t __attribute__((ext_vector_type(4)));
 typedef float  float4_t  __attribute__((ext_vector_type(4)));
+
+typedef _Float16 half4_t __attribute__((ext_vector_type(4)));
+typedef short    short4_t __attribute__((ext_vector_type(4)));
+typedef uint32_t uint2_t  __attribute__((ext_vector_type(2)));
 
 constexpr int TILE = 16;
 constexpr int WKV_PREFILL_MAX_TOKENS = 4096;   // prompt length the compression stages in LDS (WKV_MAX_PROMPT)
@@ -62,6 +69,43 @@ constexpr int XCDS = 8;
 __device__ __forceinline__ int xcd_unit(unsigned b, int groups) { return (int)((b >> 3) / groups) * XCDS + (int)(b & 7); }
 inline int xcd_grid(int units, int groups) { return (units + XCDS - 1) / XCDS * XCDS * groups; }
 
+// Four softmax weights p >= 0, each as two 16-bit numbers of the cache format with hi + lo = p to
+// 2^-16 relative (fp16: 2^-21), packed as MFMA operands, so that P.V can run on the 16-bit matrix
+// instruction without costing accuracy.  hi is p cut to the format's significand (a mask: exact in
+// the format), lo is the exact remainder, cut again.  (fp16 weights below 2^-14 lose bits below
+// 2^-24 absolute.)  No conversion of a double to 16 bits appears here: the compiler expands that
+// one into some thirty integer instructions.
+typedef _Float16 half2v_t __attribute__((ext_vector_type(2)));
+template <class TT> __device__ __forceinline__ void split16x4(const float (&p)[4], uint2_t& hi, uint2_t& lo) {
+    float h[4], l[4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        const uint32_t keep = __is_same(TT, TF16) ? 0xFFFFE000u : 0xFFFF0000u;
+        h[r] = __builtin_bit_cast(float, __builtin_bit_cast(uint32_t, p[r]) & keep);
+        l[r] = p[r] - h[r];
+    }
+    if constexpr (__is_same(TT, TF16)) {
+        hi = uint2_t{ __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(h[0], h[1])),
+                      __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(h[2], h[3])) };
+        lo = uint2_t{ __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(l[0], l[1])),
+                      __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(l[2], l[3])) };
+    } else {
+        auto pack = [](float a, float b) {                   // the upper halves of two words
+            return __builtin_amdgcn_perm(__builtin_bit_cast(uint32_t, b), __builtin_bit_cast(uint32_t, a), 0x07060302u);
+        };
+        hi = uint2_t{ pack(h[0], h[1]), pack(h[2], h[3]) };
+        lo = uint2_t{ pack(l[0], l[1]), pack(l[2], l[3]) };
+    }
+}
+
+// D += A.B with 16-bit operands (four per lane, packed in two words) and fp32 accumulation
+template <class TT> __device__ __forceinline__ float4_t mfma16(uint2_t a, uint2_t b, float4_t c) {
+    if constexpr (__is_same(TT, TF16))
+        return __builtin_amdgcn_mfma_f32_16x16x16f16(__builtin_bit_cast(half4_t, a), __builtin_bit_cast(half4_t, b), c, 0, 0, 0);
+    else
+        return __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(short4_t, a), __builtin_bit_cast(short4_t, b), c, 0, 0, 0);
+}
+
 __device__ __forceinline__ double xor_max(double v, int mask) { return fmax(v, __shfl_xor(v, mask)); }
 
 // S^T tile: rows = 16 keys, columns = 16 queries; register r of lane (g, x) = key g + 4r, query x.
@@ -84,7 +128,7 @@ __device__ __forceinline__ double4_t logits_tile(const uint32_t (&kfrag)[D / 8],
 // q, k, v, out: [P][units][D] (token-major, as a decode step sees them one token at a time).
 // lse: [units][P].  One workgroup = 4 waves = 4 consecutive query tiles of one unit.
 template <class TT, int D>
-__global__ __launch_bounds__(256)
+__global__ __launch_bounds__(256, 2)
 void wkv_prefill_rows(const void* __restrict__ q_, const void* __restrict__ k_, const void* __restrict__ v_,
                       void* __restrict__ out_, double* __restrict__ lse, int P, int units)
 {
@@ -147,30 +191,42 @@ void wkv_prefill_rows(const void* __restrict__ q_, const void* __restrict__ k_, 
         tmax = xor_max(xor_max(tmax, 16), 32);
         const double mnew = fmax(mrow, tmax);                 // finite: key 16 kt + 0 <= every query of a later tile,
                                                               // and on the diagonal key x is attended by query x
-        const double resc = exp(mrow - mnew);                 // 0 on the first tile (mrow = -inf)
+        // A running maximum that has not moved needs no rescaling, and after the first few key
+        // tiles of a row it rarely moves: the rescaling (an exp, the running sum and all output
+        // accumulators of the wave) is skipped unless some query of the tile needs it.
+        if (__any(mnew > mrow)) {
+            const double resc = exp(mrow - mnew);             // 0 on the first tile (mrow = -inf), 1 where nothing moved
+            lrow *= resc;
+            mrow = mnew;
+            const float rf = (float)resc;                     // the output rows this lane holds (queries 4g + r') by their own factor
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const float f = __shfl(rf, 4 * g + r);
+#pragma unroll
+                for (int e = 0; e < NE; ++e) o[e][r] *= f;
+            }
+        }
         float p[4];
         double psum = 0.0;
 #pragma unroll
-        for (int r = 0; r < 4; ++r) { const double e = exp(s[r] - mnew); psum += e; p[r] = (float)e; }
+        for (int r = 0; r < 4; ++r) { const double e = exp(s[r] - mrow); psum += e; p[r] = (float)e; }
         psum += __shfl_xor(psum, 16);
         psum += __shfl_xor(psum, 32);
-        lrow = lrow * resc + psum;
-        mrow = mnew;
-        // rescale the output rows this lane holds (queries 4g + r') by their own factor
-        const float rf = (float)resc;
+        lrow += psum;
+        // O[query][column] += sum over keys P[query][key] V[key][column] with the 16-bit matrix
+        // instruction (k = 16 keys at once): lane (g, x) supplies k-slots 4g + r, which stand for the
+        // keys g + 4r it already holds -- as A operand P[query x][key g + 4r], as B operand
+        // V[key g + 4r][column NE*x + e], the raw cache values.  P goes in as hi + lo.
+        uint2_t pa_hi, pa_lo;
+        split16x4<TT>(p, pa_hi, pa_lo);
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            const float f = __shfl(rf, 4 * g + r);
-#pragma unroll
-            for (int e = 0; e < NE; ++e) o[e][r] *= f;
+        for (int e = 0; e < NE; ++e) {
+            const uint32_t sel = (e & 1) ? 0x07060302u : 0x05040100u;      // high / low halves of two words
+            const uint2_t vb = { __builtin_amdgcn_perm(vfrag[1][e >> 1], vfrag[0][e >> 1], sel),
+                                 __builtin_amdgcn_perm(vfrag[3][e >> 1], vfrag[2][e >> 1], sel) };
+            o[e] = mfma16<TT>(pa_hi, vb, o[e]);
+            o[e] = mfma16<TT>(pa_lo, vb, o[e]);
         }
-        // O[query][column] += sum over keys P[query][key] V[key][column]: A = P (k index = g: key g + 4r
-        // in step r), B = V[key g + 4r][column NE*x + e]
-#pragma unroll
-        for (int r = 0; r < 4; ++r)
-#pragma unroll
-            for (int e = 0; e < NE; ++e)
-                o[e] = __builtin_amdgcn_mfma_f32_16x16x4f32(p[r], frag_elem<TT>(vfrag[r], e), o[e], 0, 0, 0);
     }
 
     // o_t = O / l, log-sum-exp = m + log l
