@@ -339,8 +339,9 @@ void wkv_prefill_scores(const void* __restrict__ q_, const void* __restrict__ k_
 // merges (Algorithm 1) in fp64, with no dependent chain of row updates.  Rows are rounded to the
 // cache format once, when they are written.
 //
-// LDS: sc[P] score, later weight | ae[P] edge coefficient | a0[P] own coefficient | slot[P] |
-//      wcnt[NT] | rk[P] rank (16 bit) | par[P] parent (16 bit).
+// LDS: sc[P] score, then list products, finally weight | ae[P] f, then edge coefficient | a0[P] g, then
+//      own coefficient | slot[P] | wcnt[NT] | rk[P] rank (16 bit) | par[P] parent (16 bit) |
+//      ptr[P] list successor (16 bit) | bmax[64].  The sort keys borrow ae[], a0[] and slot[].
 template <class TT, int D>
 __global__ __launch_bounds__(1024)
 void wkv_prefill_compress(WkvCache c, const void* __restrict__ k_, const void* __restrict__ v_,
@@ -368,7 +369,8 @@ void wkv_prefill_compress(WkvCache c, const void* __restrict__ k_, const void* _
     int32_t*  wcnt = slot + P;
     uint16_t* rk   = reinterpret_cast<uint16_t*>(wcnt + NT);
     uint16_t* par  = rk + P;
-    constexpr int TOP = 0x10000;                              // a survivor ranks above every removed token
+    uint16_t* ptr  = par + P;                                 // successor in the list a product runs along
+    uint16_t* bmax = ptr + P;                                 // [64] highest rank in a block of 64 tokens
     const int L = (P < m) ? P : m;
     const int nrem = P - L;                                   // tokens to remove
     const int lo = c.n_sink, hi = P - c.R;                    // candidates: lo <= token < hi
@@ -380,21 +382,43 @@ void wkv_prefill_compress(WkvCache c, const void* __restrict__ k_, const void* _
         sc[i] = s;
     }
     __syncthreads();
-    // rank among the candidates by (score, token); the nrem lowest are removed
-    for (int i = tid; i < P; i += NT) {
-        int rank = 0xFFFF;
-        if (nrem > 0 && i >= lo && i < hi) {
-            const double si = sc[i];
-            rank = 0;
-            for (int k = lo; k < hi; ++k) {
-                const double sk = sc[k];
-                rank += (sk < si || (sk == si && k < i)) ? 1 : 0;
+    // rank among the candidates by (score, token); the nrem lowest are removed.  A bitonic sort of
+    // (score bits, token) in LDS (the key arrays borrow ae[], a0[] and slot[], not yet in use).
+    for (int i = tid; i < P; i += NT) rk[i] = 0xFFFF;
+    if (nrem > 0) {
+        unsigned long long* key = reinterpret_cast<unsigned long long*>(ae);   // [N2]
+        uint16_t* kid = reinterpret_cast<uint16_t*>(slot);                     // [N2]
+        int N2 = 1;
+        while (N2 < P) N2 <<= 1;
+        for (int i = tid; i < N2; i += NT) {
+            unsigned long long kb64 = ~0ull;                                   // not a candidate, or padding: sorts last
+            if (i >= lo && i < hi) {
+                const unsigned long long bits = (unsigned long long)__double_as_longlong(sc[i]);
+                kb64 = (bits >> 63) ? ~bits : (bits | 0x8000000000000000ull);  // order of the doubles as order of integers
+                if (kb64 == ~0ull) kb64 = ~0ull - 1;                           // (no score maps there; keep the sentinel unique)
             }
-            if (rank >= nrem) rank = 0xFFFF;
+            key[i] = kb64;
+            kid[i] = (uint16_t)i;
         }
-        rk[i] = (uint16_t)rank;
-        slot[i] = (rank != 0xFFFF) ? -1 : 0;
+        __syncthreads();
+        for (int k = 2; k <= N2; k <<= 1) {
+            for (int j = k >> 1; j > 0; j >>= 1) {
+                for (int t = tid; t < (N2 >> 1); t += NT) {
+                    const int i = ((t & ~(j - 1)) << 1) | (t & (j - 1)), l = i | j;
+                    const unsigned long long ki = key[i], kl = key[l];
+                    const uint16_t di = kid[i], dl = kid[l];
+                    const bool gt = ki > kl || (ki == kl && di > dl);
+                    if (gt == ((i & k) == 0)) { key[i] = kl; key[l] = ki; kid[i] = dl; kid[l] = di; }
+                }
+                __syncthreads();
+            }
+        }
+        for (int r = tid; r < nrem; r += NT) rk[kid[r]] = (uint16_t)r;         // the nrem lowest keys are candidates
+        __syncthreads();
+    } else {
+        __syncthreads();
     }
+    for (int i = tid; i < P; i += NT) slot[i] = (rk[i] != 0xFFFF) ? -1 : 0;
     __syncthreads();
     // survivors get consecutive slots in token order: exclusive scan over the keep flags
     const int per = (P + NT - 1) / NT;
@@ -427,64 +451,140 @@ void wkv_prefill_compress(WkvCache c, const void* __restrict__ k_, const void* _
 
     const bool merging = c.merge_mode == 0 && nrem > 0;
     if (merging) {
-        // parent of a removed token: the nearest token to its right that outranks it
-        for (int i = tid; i < P; i += NT) {
-            int k = i;
-            if (slot[i] < 0) { const int ri = rk[i]; k = i + 1; while (slot[k] < 0 && rk[k] < ri) ++k; }
-            par[i] = (uint16_t)k;                             // a survivor is its own parent
+        // Parent of a removed token: the nearest token to its right that outranks it (survivors
+        // outrank everything: rank 0xFFFF); also the nearest one to its LEFT that outranks it.  Both by
+        // a search that skips whole blocks of 64 tokens whose highest rank is too low, so a token
+        // looks at < 200 entries however long the runs are.
+        constexpr int NIL = 0xFFFF;
+        const int nblk = (P + 63) >> 6;
+        for (int b = wid; b < nblk; b += NW) {
+            const int i = b * 64 + lane;
+            int r = (i < P) ? (int)rk[i] : 0;
+#pragma unroll
+            for (int off = 32; off > 0; off >>= 1) r = max(r, __shfl_xor(r, off));
+            if (lane == 0) bmax[b] = (uint16_t)r;
         }
         __syncthreads();
-        // coefficients.  First f of every removed token with respect to its parent (one division per
-        // token, kept in ae[]); then the products over children and over later siblings, which are
-        // multiplications only -- a survivor that takes in thousands of tokens has as many children,
-        // and each of them looks at all the others.  The children of p sit in the stretch left of p
-        // that p outranks.
+        for (int i = tid; i < P; i += NT) {
+            int right = i, left = NIL;                        // a survivor is its own parent
+            if (slot[i] < 0) {
+                const int ri = rk[i];
+                {
+                    const int e = min((i | 63) + 1, P);
+                    int k = i + 1;
+                    while (k < e && rk[k] <= ri) ++k;
+                    if (k == e) {                              // a survivor lies to the right (the newest tokens are never removed)
+                        int b = (i >> 6) + 1;
+                        while (b < nblk - 1 && bmax[b] <= ri) ++b;
+                        k = b * 64;
+                        while (k < P - 1 && rk[k] <= ri) ++k;
+                    }
+                    right = k;
+                }
+                {
+                    const int e = (i & ~63) - 1;
+                    int k = i - 1;
+                    while (k > e && rk[k] <= ri) --k;
+                    if (k == e) {
+                        int b = (i >> 6) - 1;
+                        while (b >= 0 && bmax[b] <= ri) --b;
+                        if (b >= 0) { k = b * 64 + 63; while (rk[k] <= ri) --k; }   // bmax[b] > ri: the scan ends inside block b
+                        else k = -1;
+                    }
+                    left = (k >= 0) ? k : NIL;
+                }
+            }
+            par[i] = (uint16_t)right;
+            ptr[i] = (uint16_t)left;
+        }
+        __syncthreads();
+        // f and g of every removed token with respect to its parent (one division each): f -> ae[], g -> a0[]
         for (int i = tid; i < P; i += NT) {
             if (slot[i] >= 0) continue;
-            const double sp = sc[par[i]], den = sc[i] + sp;
+            const double sp = sc[par[i]], si = sc[i], den = si + sp;
             ae[i] = (den > 0.0) ? sp / den : 0.5;
+            a0[i] = (den > 0.0) ? si / den : 0.5;
             if (!(den > 0.0)) atomicAdd(&c.status[0], 1);
         }
         __syncthreads();
+        // Products along lists by pointer jumping: every removed token i has a successor (held in
+        // ptr[i], NIL at the end); on return sc[i] = product of val[] over all tokens after i in its
+        // list.  log2(list length) rounds, each token's update held in registers across a barrier.
+        // sc[] (the scores) is free from here on.
         constexpr int MAXTOK = (WKV_PREFILL_MAX_TOKENS + 1023) / 1024;   // tokens per thread
-        double edge[MAXTOK];
-#pragma unroll
-        for (int kk = 0; kk < MAXTOK; ++kk) {
-            const int i = tid + kk * NT;
-            edge[kk] = 0.0;
-            if (i >= P) continue;
-            const bool removed = slot[i] < 0;
-            {   // own coefficient of token i: product of f over its children
-                const int ri = removed ? (int)rk[i] : TOP;
-                double prod = 1.0;
-                for (int k = i - 1; k >= 0 && slot[k] < 0 && rk[k] < ri; --k)
-                    if (par[k] == i) prod *= ae[k];
-                a0[i] = prod;
+        auto list_products = [&](const double* val) {
+            for (int i = tid; i < P; i += NT) {
+                const int j = (slot[i] < 0) ? (int)ptr[i] : NIL;
+                sc[i] = (j != NIL) ? val[j] : 1.0;
             }
-            if (removed) {   // edge coefficient of token i within its parent: g_i times f of the later siblings
-                const int p = par[i], ri = rk[i];
-                const int rp = (slot[p] < 0) ? (int)rk[p] : TOP;
-                const double sp = sc[p], si = sc[i], den = si + sp;
-                double prod = (den > 0.0) ? si / den : 0.5;
-                for (int k = p - 1; k >= 0 && slot[k] < 0 && rk[k] < rp; --k)
-                    if (par[k] == p && rk[k] > ri) prod *= ae[k];
-                edge[kk] = prod;
-            }
-        }
-        __syncthreads();
+            __syncthreads();
+            for (;;) {
+                double wn[MAXTOK];
+                int jn[MAXTOK];
+                int pending = 0;
 #pragma unroll
-        for (int kk = 0; kk < MAXTOK; ++kk) {
-            const int i = tid + kk * NT;
-            if (i < P && slot[i] < 0) ae[i] = edge[kk];
-        }
-        __syncthreads();
-        // weight of every removed token's raw value in its survivor's row (scores are no longer needed)
+                for (int kk = 0; kk < MAXTOK; ++kk) {
+                    const int i = tid + kk * NT;
+                    jn[kk] = NIL;
+                    wn[kk] = 1.0;
+                    if (i < P && slot[i] < 0) {
+                        const int j = ptr[i];
+                        wn[kk] = sc[i];
+                        if (j != NIL) { wn[kk] *= sc[j]; jn[kk] = ptr[j]; pending |= (jn[kk] != NIL) ? 1 : 0; }
+                    }
+                }
+                __syncthreads();
+#pragma unroll
+                for (int kk = 0; kk < MAXTOK; ++kk) {
+                    const int i = tid + kk * NT;
+                    if (i < P && slot[i] < 0) { sc[i] = wn[kk]; ptr[i] = (uint16_t)jn[kk]; }
+                }
+                if (!__syncthreads_or(pending)) break;
+            }
+        };
+        // Siblings.  The children of p, from p - 1 leftwards, have ascending rank, i.e. they are merged
+        // into p in that order; the one after child i is the nearest token on i's left that outranks
+        // i, as long as it does not outrank p as well.  ptr[] holds that left neighbour: cut the lists.
         for (int i = tid; i < P; i += NT) {
             if (slot[i] >= 0) continue;
-            double w = ae[i] * a0[i];
-            for (int q = par[i]; slot[q] < 0; q = par[q]) w *= ae[q];
-            sc[i] = w;
+            const int l = ptr[i];
+            if (l != NIL && rk[l] >= rk[par[i]]) ptr[i] = NIL;     // (a survivor has rank 0xFFFF)
         }
+        __syncthreads();
+        list_products(ae);                                     // sc[i] = product of f over the siblings merged after i
+        // edge coefficient of a removed token within its parent: g_i times the f of the later siblings;
+        // own coefficient of any token: the f of all its children = f of the first child (the token on
+        // its left, if that is a child) times the f of that child's later siblings.
+        {
+            double edge[MAXTOK], own[MAXTOK];
+#pragma unroll
+            for (int kk = 0; kk < MAXTOK; ++kk) {
+                const int i = tid + kk * NT;
+                edge[kk] = 0.0; own[kk] = 1.0;
+                if (i >= P) continue;
+                if (slot[i] < 0) edge[kk] = a0[i] * sc[i];
+                if (i > 0 && slot[i - 1] < 0 && par[i - 1] == i) own[kk] = ae[i - 1] * sc[i - 1];
+            }
+            __syncthreads();
+#pragma unroll
+            for (int kk = 0; kk < MAXTOK; ++kk) {
+                const int i = tid + kk * NT;
+                if (i >= P) continue;
+                if (slot[i] < 0) ae[i] = edge[kk];
+                a0[i] = own[kk];
+            }
+        }
+        // Ancestors: the weight of a raw token in its survivor's row is its own coefficient times the
+        // edge coefficients up the tree.
+        for (int i = tid; i < P; i += NT) {
+            if (slot[i] >= 0) continue;
+            const int q = par[i];
+            ptr[i] = (slot[q] < 0) ? (uint16_t)q : (uint16_t)NIL;
+        }
+        __syncthreads();
+        list_products(ae);                                     // sc[i] = product of the edge coefficients of i's removed ancestors
+        for (int i = tid; i < P; i += NT)
+            if (slot[i] < 0) sc[i] *= ae[i] * a0[i];
         __syncthreads();
     }
     // acc += sum over rows k = first, first + stride, ... <= last of weight(k) * V_k, where the last
@@ -585,7 +685,7 @@ hipError_t run(const WkvCache& c, const void* q, const void* k, const void* v, v
 
 }  // namespace
 
-size_t wkv_prefill_lds_bytes(int P) { return (size_t)P * 32 + 1024 * 4; }
+size_t wkv_prefill_lds_bytes(int P) { return (size_t)P * 34 + 1024 * 4 + 64 * 2; }
 
 hipError_t wkv_launch_prefill(const WkvCache& c, int dtype, int head_dim, const void* q, const void* k,
                               const void* v, void* out, double* lse, double* a, int P, hipStream_t stream)
