@@ -136,11 +136,15 @@ def check_cache_state(cache, orc, sel, cfg, T):
     return v_exact
 
 
-def gpu_prefill(cfg, P, layer=0, units_sel=None, want_out=True, **create_kw):
-    """Prefill a fresh handle with the first P tokens of the stream.  Returns dict(out [P,U',d] f64,
-    cache, inputs of the selected units as exact fp32, the device tensors of the whole stream)."""
-    st = synth.Stream(cfg, layer)
-    q, k, v = st.steps(0, cfg.steps)
+def gpu_prefill(cfg, P, layer=0, units_sel=None, want_out=True, arrays=None, **create_kw):
+    """Prefill a fresh handle with the first P tokens of the stream (or of `arrays`, fp32
+    [steps, units, d] triples made by hand, rounded to storage here).  Returns dict(out [P,U',d]
+    f64, cache, inputs of the selected units as exact fp32, the device tensors of the whole stream)."""
+    if arrays is None:
+        st = synth.Stream(cfg, layer)
+        q, k, v = st.steps(0, cfg.steps)
+    else:
+        q, k, v = (synth.to_storage(np.ascontiguousarray(x, dtype=np.float32), cfg.dtype) for x in arrays)
     create_kw.setdefault("split", 1)
     cache = wkv.Cache(cfg.batch, cfg.heads, cfg.head_dim, cfg.budget, cfg.recent,
                       synth.DTYPE_CODE[cfg.dtype], **create_kw)

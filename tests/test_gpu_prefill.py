@@ -64,6 +64,41 @@ def test_long_runs_of_removed_tokens():
     _run(cfg, 1200, decode_steps=10)
 
 
+def _directed(cfg, slope, seed):
+    """Prompts whose average scores are monotone in the token index: every query and key points
+    along one direction per unit, and the logit of token i is proportional to slope * i.  slope > 0:
+    every row attends to its newest tokens, abar_i ~ 1 / (P - i) ascends; slope < 0: every row
+    attends to the oldest tokens, abar_i ~ exp(-c i) descends."""
+    rng = np.random.default_rng(seed)
+    T, U, d = cfg.steps, cfg.units, cfg.head_dim
+    u = rng.standard_normal((1, U, d)).astype(np.float32)
+    u *= np.sqrt(d) / np.linalg.norm(u, axis=-1, keepdims=True)
+    ramp = np.arange(T, dtype=np.float32)[:, None, None] * slope
+    q = np.broadcast_to(u, (T, U, d)) * 0.5
+    k = u * ramp
+    v = rng.standard_normal((T, U, d)).astype(np.float32)
+    return q, k, v
+
+
+@pytest.mark.parametrize("slope", [0.02, -0.02])
+def test_monotone_scores_chains_and_fans(slope):
+    """The two extreme shapes of the merge forest.  Ascending scores: every removed token folds
+    into its right neighbour, one chain as long as the run (the weights are products up the
+    chain).  Descending scores: the newest removed token goes first and every removed token is a
+    child of the one survivor on the right (the weights are products over later siblings).  Runs
+    of ~900 tokens span many 64-token blocks of the parent search."""
+    cfg = synth.StreamConfig("pre-mono", 8600, 1, 3, 64, "fp16", 1000, 24, 4)
+    g = parity.gpu_prefill(cfg, 990, arrays=_directed(cfg, slope, 8600))
+    try:
+        stats = parity.compare_prefill(cfg, g, decode_steps=10)
+        pos = g["cache"].state(wkv.WKV_POS)
+        gaps = np.diff(np.concatenate([np.full((pos.shape[0], 1), -1), pos], axis=1), axis=1)
+        assert gaps.max() > 800, "expected one long run of removed tokens"
+    finally:
+        g["cache"].close()
+    print(f"\n  slope {slope}: {stats}, longest run {int(gaps.max())}", flush=True)
+
+
 def test_prefill_then_sliced_decode():
     cfg = synth.StreamConfig("pre-split", 8400, 1, 2, 128, "fp16", 700, 300, 16)
     _run(cfg, 650, decode_steps=50, split=4)
