@@ -1,5 +1,5 @@
 // Host side of libwkv: handle management, argument checking, state readback.
-// The arithmetic of the method lives in wkv_step.hip; nothing here computes
+// The arithmetic of the method lives in the kernels (wkv_step.hip, wkv_split.hip, wkv_prefill.hip); nothing here computes
 // attention, scores or merges.  See include/wkv.h for the contract.
 #include "../../include/wkv.h"
 #include "wkv_internal.h"
