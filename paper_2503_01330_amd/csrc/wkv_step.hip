@@ -35,7 +35,8 @@
 // indices, links) is requested before the streaming loop starts, wave-level
 // reductions use DPP row operations plus v_readlane instead of LDS permutes,
 // per-wave results are combined by one DPP row reduction per wave, and the two
-// V rows of the merge are taken from the registers they were streamed into.
+// V rows of the merge are requested by wave 0 the moment it knows which they are,
+// well ahead of the barrier after which it needs them.
 #include "wkv_internal.h"
 #include <type_traits>
 
@@ -76,8 +77,8 @@ namespace {
 //
 // DED: wave 0 streams K like every other wave but takes no V rows: the V phase is spread over the
 // other waves (NG - 4 groups), and wave 0 has only the bookkeeping between the two barriers.
-// Without it wave 0 does the bookkeeping (~2.6 us for 411 entries) and then its share of V, and
-// the other 15 waves wait ~1.7 us for it at the second barrier.  Used with 1024-thread workgroups.
+// Without it wave 0 does the bookkeeping (~2 us for 411 entries) and then its share of V, and
+// the other waves wait for it at the second barrier.  Chosen by the host (dedicated_wave below).
 template <class TT, int D, int U, int MAXT, bool SEP, bool DED>
 __global__ __launch_bounds__(MAXT)
 void wkv_step_kernel(WkvCache c, const void* __restrict__ q_, const void* __restrict__ k_,
@@ -224,9 +225,9 @@ void wkv_step_kernel(WkvCache c, const void* __restrict__ q_, const void* __rest
     logits(nchunks - 1);
     [[maybe_unused]] uint32_t vin[NW32];                    // SEP: the incoming value in row layout
     if constexpr (SEP) load_words<NW32>(vu + sub * LANEB, vin);
-    // stage what the bookkeeping needs (these loads are older than the K rows: they have arrived): score sums, token indices, and token order as a linked
-    // list (nl[i] = entry that follows entry i; the newest cached token is followed by the
-    // incoming one, entry Lc)
+    // stage what the bookkeeping needs (these loads are older than the K rows: they have
+    // arrived): score sums, token indices, and token order as a linked list (nl[i] = entry that
+    // follows entry i; the newest cached token is followed by the incoming one, entry Lc)
 #pragma unroll
     for (int k = 0; k < MAXPT; ++k) {
         const int i = tid + k * NT;
@@ -511,11 +512,17 @@ inline int row_slots(int m, int ch, bool* sep)
 
 // Wave 0 is kept free of V rows (DED at the kernel) in the 1024-thread workgroups always; in
 // the smaller ones when the launch is not large enough for many workgroups per compute unit to
-// overlap each other's serial stretches.  Measured (512 threads, d = 128, 16-bit): 384 units
-// x 410 slots 23.6 -> 21.9 us, 1024 x 520 47.2 -> 45.3 (0.79 of peak), 2048 x 512 102.7 -> 103.4.
-inline bool dedicated_wave(const WkvCache& c, int threads, size_t row_bytes)
+// overlap each other's serial stretches, and the V rows still fit the same number of chunks
+// with four groups fewer.  Measured (512 threads, d = 128, 16-bit, us per step with / without):
+// 384 units x 410 slots 21.1 / 22.3, 512 x 410 23.8 / 24.8, 1024 x 520 55.0 / 55.2, 2048 x 512
+// 102.1 / 102.4; one more chunk of V: 512 x 1024 54.2 / 53.9, 4096 x 256 150.6 / 104.0.
+inline bool dedicated_wave(const WkvCache& c, int threads, size_t row_bytes, int rows_per_group, bool sep)
 {
-    return threads > 512 || (size_t)c.units * (size_t)(c.m + 1) * row_bytes * 2 <= (size_t)400 << 20;
+    if (threads > 512) return true;
+    const int ls = sep ? c.m : c.m + 1, ng = threads / ROW_LANES;
+    const int chunk = ng * rows_per_group, chunk_v = (ng - 4) * rows_per_group;
+    const bool same_chunks = (ls + chunk - 1) / chunk == (ls + chunk_v - 1) / chunk_v;
+    return same_chunks && (size_t)c.units * (size_t)(c.m + 1) * row_bytes * 2 <= (size_t)400 << 20;
 }
 
 template <class TT, int D, int U, int MAXT>
@@ -563,7 +570,7 @@ hipError_t launch_u(const WkvCache& c, int threads, size_t lds, bool sep, const 
                     const void* v, void* out, int t, hipStream_t stream)
 {
     if constexpr (MAXT <= 512) {
-        if (!dedicated_wave(c, threads, (size_t)D * TT::BYTES))
+        if (!dedicated_wave(c, threads, (size_t)D * TT::BYTES, U, sep))
             return launch_ud<TT, D, U, MAXT, false>(c, threads, lds, sep, q, k, v, out, t, stream);
     }
     return launch_ud<TT, D, U, MAXT, true>(c, threads, lds, sep, q, k, v, out, t, stream);
