@@ -132,6 +132,37 @@ template <class X> __device__ __forceinline__ X row_allsum(X x) {
     return x;
 }
 
+// Exchange between the 16-lane rows of a wave: v_permlane16_swap / v_permlane32_swap (gfx950) hand
+// every lane, in one VALU instruction and without a trip through the LDS crossbar, its own value
+// and that of the lane 16 (32) lanes away.  Called with the same register twice they return, as
+// measured on the hardware, .x = the value held by the even row (the lower half) of each pair and
+// .y = that of the odd row (the upper half), identical in both lanes of a pair.  Summing or taking
+// the maximum of .x and .y is the butterfly step x op shfl_xor(x, W), with the same bits in both
+// partners (the operands are taken in the same order on both sides).
+typedef unsigned uint2v_t __attribute__((ext_vector_type(2)));
+template <int W> __device__ __forceinline__ void lane_pair(unsigned v, unsigned& even, unsigned& odd) {
+    static_assert(W == 16 || W == 32, "rows 16 apart or halves 32 apart");
+    uint2v_t p;
+    if constexpr (W == 16) p = __builtin_amdgcn_permlane16_swap(v, v, false, false);
+    else p = __builtin_amdgcn_permlane32_swap(v, v, false, false);
+    even = p.x; odd = p.y;        // as scalars: __builtin_bit_cast applied to p.y itself reads p.x (hipcc of ROCm 7.2)
+}
+template <int W> __device__ __forceinline__ void lane_pair(float v, float& even, float& odd) {
+    unsigned a, b;
+    lane_pair<W>(__builtin_bit_cast(unsigned, v), a, b);
+    even = __builtin_bit_cast(float, a); odd = __builtin_bit_cast(float, b);
+}
+template <int W> __device__ __forceinline__ void lane_pair(double v, double& even, double& odd) {
+    unsigned la, lb, ha, hb;
+    lane_pair<W>((unsigned)__double2loint(v), la, lb);
+    lane_pair<W>((unsigned)__double2hiint(v), ha, hb);
+    even = __hiloint2double((int)ha, (int)la); odd = __hiloint2double((int)hb, (int)lb);
+}
+template <int W, class X> __device__ __forceinline__ X pair_sum(X v) { X a, b; lane_pair<W>(v, a, b); return a + b; }
+template <int W> __device__ __forceinline__ double pair_max(double v) { double a, b; lane_pair<W>(v, a, b); return fmax(a, b); }
+// over the four rows of a wave: lanes x, x + 16, x + 32, x + 48
+template <class X> __device__ __forceinline__ X rows_sum(X v) { return pair_sum<32>(pair_sum<16>(v)); }
+
 __device__ __forceinline__ float  soft_exp(float x)  { return __expf(x); }
 __device__ __forceinline__ double soft_exp(double x) { return exp(x); }
 

@@ -106,7 +106,6 @@ template <class TT> __device__ __forceinline__ float4_t mfma16(uint2_t a, uint2_
         return __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(short4_t, a), __builtin_bit_cast(short4_t, b), c, 0, 0, 0);
 }
 
-__device__ __forceinline__ double xor_max(double v, int mask) { return fmax(v, __shfl_xor(v, mask)); }
 
 // S^T tile: rows = 16 keys, columns = 16 queries; register r of lane (g, x) = key g + 4r, query x.
 // Both operands are the exact storage values; the softmax scale is applied to the four results.
@@ -188,7 +187,7 @@ void wkv_prefill_rows(const void* __restrict__ q_, const void* __restrict__ k_, 
             for (int r = 0; r < 4; ++r) if (g + 4 * r > x) s[r] = -INFINITY;
         }
         double tmax = fmax(fmax(s[0], s[1]), fmax(s[2], s[3]));
-        tmax = xor_max(xor_max(tmax, 16), 32);
+        tmax = pair_max<32>(pair_max<16>(tmax));               // over the four lane groups: all 16 keys of the tile
         const double mnew = fmax(mrow, tmax);                 // finite: key 16 kt + 0 <= every query of a later tile,
                                                               // and on the diagonal key x is attended by query x
         // A running maximum that has not moved needs no rescaling, and after the first few key
@@ -210,8 +209,7 @@ void wkv_prefill_rows(const void* __restrict__ q_, const void* __restrict__ k_, 
         double psum = 0.0;
 #pragma unroll
         for (int r = 0; r < 4; ++r) { const double e = exp(s[r] - mrow); psum += e; p[r] = (float)e; }
-        psum += __shfl_xor(psum, 16);
-        psum += __shfl_xor(psum, 32);
+        psum = rows_sum(psum);
         lrow += psum;
         // O[query][column] += sum over keys P[query][key] V[key][column] with the 16-bit matrix
         // instruction (k = 16 keys at once): lane (g, x) supplies k-slots 4g + r, which stand for the

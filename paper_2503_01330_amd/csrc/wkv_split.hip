@@ -179,12 +179,9 @@ void wkv_split_kernel(WkvCache c, WkvSplit sp, const void* __restrict__ q_, cons
     weighted_sum(0);
     for (int ch = 1; ch < nchunks; ++ch) { request(vw, Vc, vu, ch); weighted_sum(ch); }
     {
+        l_run = rows_sum(l_run);                           // over the wave's four groups
 #pragma unroll
-        for (int off = 16; off <= 32; off <<= 1) {
-            l_run += __shfl_xor(l_run, off);
-#pragma unroll
-            for (int e = 0; e < EPL; ++e) acc[e] += __shfl_xor(acc[e], off);
-        }
+        for (int e = 0; e < EPL; ++e) acc[e] = rows_sum(acc[e]);
         if (lane < ROW_LANES) {
 #pragma unroll
             for (int e = 0; e < EPL; ++e) part[wid * D + lane * EPL + e] = acc[e];

@@ -393,12 +393,9 @@ void wkv_step_kernel(WkvCache c, const void* __restrict__ q_, const void* __rest
         S acc_w[EPL];
 #pragma unroll
         for (int e = 0; e < EPL; ++e) acc_w[e] = acc[e];
+        l_w = rows_sum(l_w);                               // over the wave's four groups
 #pragma unroll
-        for (int off = 16; off <= 32; off <<= 1) {
-            l_w += __shfl_xor(l_w, off);
-#pragma unroll
-            for (int e = 0; e < EPL; ++e) acc_w[e] += __shfl_xor(acc_w[e], off);
-        }
+        for (int e = 0; e < EPL; ++e) acc_w[e] = rows_sum(acc_w[e]);
         if (lane < ROW_LANES) {
 #pragma unroll
             for (int e = 0; e < EPL; ++e) part[wid * D + lane * EPL + e] = acc_w[e];
