@@ -69,13 +69,16 @@ constexpr int XCDS = 8;
 __device__ __forceinline__ int xcd_unit(unsigned b, int groups) { return (int)((b >> 3) / groups) * XCDS + (int)(b & 7); }
 inline int xcd_grid(int units, int groups) { return (units + XCDS - 1) / XCDS * XCDS * groups; }
 
-// Four softmax weights p >= 0, each as two 16-bit numbers of the cache format with hi + lo = p to
-// 2^-16 relative (fp16: 2^-21), packed as MFMA operands, so that P.V can run on the 16-bit matrix
-// instruction without costing accuracy.  hi is p cut to the format's significand (a mask: exact in
-// the format), lo is the exact remainder, cut again.  (fp16 weights below 2^-14 lose bits below
-// 2^-24 absolute.)  No conversion of a double to 16 bits appears here: the compiler expands that
+// Four softmax weights p >= 0, each as two 16-bit numbers of the cache format, packed as MFMA
+// operands, so that P.V can run on the 16-bit matrix instruction without costing accuracy.  hi is p
+// cut to the format's significand (a mask: exact in the format), lo the exact remainder brought
+// to the format: rounded to nearest for bf16 (hi + lo = p to 2^-17, and without the one-sided
+// error a cut would add up over a row), cut for fp16 (2^-22; weights below 2^-14 lose bits below
+// 2^-24 absolute).  No conversion of a double to 16 bits appears here: the compiler expands that
 // one into some thirty integer instructions.
 typedef _Float16 half2v_t __attribute__((ext_vector_type(2)));
+typedef float    float2v_t __attribute__((ext_vector_type(2)));
+typedef __bf16   bf16x2_t  __attribute__((ext_vector_type(2)));
 template <class TT> __device__ __forceinline__ void split16x4(const float (&p)[4], uint2_t& hi, uint2_t& lo) {
     float h[4], l[4];
 #pragma unroll
@@ -90,11 +93,14 @@ template <class TT> __device__ __forceinline__ void split16x4(const float (&p)[4
         lo = uint2_t{ __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(l[0], l[1])),
                       __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(l[2], l[3])) };
     } else {
-        auto pack = [](float a, float b) {                   // the upper halves of two words
+        auto pack = [](float a, float b) {                   // the upper halves of two words: exact for hi
             return __builtin_amdgcn_perm(__builtin_bit_cast(uint32_t, b), __builtin_bit_cast(uint32_t, a), 0x07060302u);
         };
+        auto round2 = [](float a, float b) {                 // v_cvt_pk_bf16_f32: to nearest even
+            return __builtin_bit_cast(uint32_t, __builtin_convertvector(float2v_t{a, b}, bf16x2_t));
+        };
         hi = uint2_t{ pack(h[0], h[1]), pack(h[2], h[3]) };
-        lo = uint2_t{ pack(l[0], l[1]), pack(l[2], l[3]) };
+        lo = uint2_t{ round2(l[0], l[1]), round2(l[2], l[3]) };
     }
 }
 

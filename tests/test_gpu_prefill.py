@@ -99,6 +99,34 @@ def test_monotone_scores_chains_and_fans(slope):
     print(f"\n  slope {slope}: {stats}, longest run {int(gaps.max())}", flush=True)
 
 
+def test_randomised_prompts():
+    """Many small random configurations (prompt length, budget, window, sinks, rule variants, head
+    size, dtype, unit count, workgroups per unit of the decode steps that follow)."""
+    g = np.random.default_rng(20250302)
+    for case in range(30):
+        dtype = ["fp16", "bf16"][int(g.integers(2))]
+        d = [64, 128][int(g.integers(2))]
+        P = int(g.integers(1, 900))
+        m = int(g.integers(1, 300))
+        R = int(g.integers(1, m + 1)) if g.random() < 0.3 else int(g.integers(1, min(m, 40) + 1))
+        n_sink = int(g.integers(0, min(5, m - R) + 1)) if g.random() < 0.4 else 0
+        mode = int(g.integers(3))       # 0 merge, 1 evict-only, 2 cumulative score
+        kw = {}
+        if n_sink:
+            kw["n_sink"] = n_sink
+        if mode >= 1:
+            kw["merge_mode"] = wkv.WKV_MERGE_NONE
+        if mode == 2:
+            kw["score_mode"] = wkv.WKV_SCORE_CUMULATIVE
+        if g.random() < 0.25 and m >= 64:
+            kw["split"] = [2, 4][int(g.integers(2))]
+        batch, heads = int(g.integers(1, 3)), int(g.integers(1, 6))
+        steps = int(g.integers(0, 9))
+        cfg = synth.StreamConfig(f"rnd{case}", 8700 + case, batch, heads, d, dtype, P + steps, m, R)
+        print(f"\n  case {case}: P={P} m={m} R={R} d={d} {dtype} units={batch * heads} {kw}", flush=True)
+        _run(cfg, P, decode_steps=steps, **kw)
+
+
 def test_prefill_then_sliced_decode():
     cfg = synth.StreamConfig("pre-split", 8400, 1, 2, 128, "fp16", 700, 300, 16)
     _run(cfg, 650, decode_steps=50, split=4)
