@@ -69,38 +69,45 @@ constexpr int XCDS = 8;
 __device__ __forceinline__ int xcd_unit(unsigned b, int groups) { return (int)((b >> 3) / groups) * XCDS + (int)(b & 7); }
 inline int xcd_grid(int units, int groups) { return (units + XCDS - 1) / XCDS * XCDS * groups; }
 
-// Four softmax weights p >= 0, each as two 16-bit numbers of the cache format, packed as MFMA
-// operands, so that P.V can run on the 16-bit matrix instruction without costing accuracy.  hi is p
-// cut to the format's significand (a mask: exact in the format), lo the exact remainder brought
-// to the format: rounded to nearest for bf16 (hi + lo = p to 2^-17, and without the one-sided
-// error a cut would add up over a row), cut for fp16 (2^-22; weights below 2^-14 lose bits below
-// 2^-24 absolute).  No conversion of a double to 16 bits appears here: the compiler expands that
-// one into some thirty integer instructions.
+// Four softmax weights p >= 0, each as a sum of 16-bit numbers of the cache format, packed as MFMA
+// operands, so that P.V can run on the 16-bit matrix instruction without costing accuracy against
+// an fp32 P.V.  Every part but the last is the running remainder cut to the format's significand
+// (a mask: exact in the format, and the next remainder is exact in fp32).
+//   fp16: two parts, 11 + 11 bits, the last one cut (2^-22; weights below 2^-14 lose bits below
+//         2^-24 absolute);
+//   bf16: three parts, 8 + 8 + 8 bits, the last one rounded to nearest.  Two parts (2^-17) were not
+//         enough: in entries that cancel to 1e-4 of their row's scale the error of the weights
+//         showed, about one element in 1e8 beyond the test's bound.
+// No conversion of a double to 16 bits appears here: the compiler expands that one into some
+// thirty integer instructions.
 typedef _Float16 half2v_t __attribute__((ext_vector_type(2)));
 typedef float    float2v_t __attribute__((ext_vector_type(2)));
 typedef __bf16   bf16x2_t  __attribute__((ext_vector_type(2)));
-template <class TT> __device__ __forceinline__ void split16x4(const float (&p)[4], uint2_t& hi, uint2_t& lo) {
-    float h[4], l[4];
-#pragma unroll
-    for (int r = 0; r < 4; ++r) {
-        const uint32_t keep = __is_same(TT, TF16) ? 0xFFFFE000u : 0xFFFF0000u;
-        h[r] = __builtin_bit_cast(float, __builtin_bit_cast(uint32_t, p[r]) & keep);
-        l[r] = p[r] - h[r];
-    }
+template <class TT> constexpr int weight_parts() { return __is_same(TT, TF16) ? 2 : 3; }
+template <class TT> __device__ __forceinline__ void split16x4(const float (&p)[4], uint2_t (&part)[weight_parts<TT>()]) {
+    constexpr uint32_t keep = __is_same(TT, TF16) ? 0xFFFFE000u : 0xFFFF0000u;
+    auto cut = [](float x) { return __builtin_bit_cast(float, __builtin_bit_cast(uint32_t, x) & keep); };
     if constexpr (__is_same(TT, TF16)) {
-        hi = uint2_t{ __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(h[0], h[1])),
-                      __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(h[2], h[3])) };
-        lo = uint2_t{ __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(l[0], l[1])),
-                      __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(l[2], l[3])) };
+        float h[4], l[4];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) { h[r] = cut(p[r]); l[r] = p[r] - h[r]; }
+        part[0] = uint2_t{ __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(h[0], h[1])),
+                           __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(h[2], h[3])) };
+        part[1] = uint2_t{ __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(l[0], l[1])),
+                           __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(l[2], l[3])) };
     } else {
-        auto pack = [](float a, float b) {                   // the upper halves of two words: exact for hi
+        auto pack = [](float a, float b) {                   // the upper halves of two words: exact for cut values
             return __builtin_amdgcn_perm(__builtin_bit_cast(uint32_t, b), __builtin_bit_cast(uint32_t, a), 0x07060302u);
         };
         auto round2 = [](float a, float b) {                 // v_cvt_pk_bf16_f32: to nearest even
             return __builtin_bit_cast(uint32_t, __builtin_convertvector(float2v_t{a, b}, bf16x2_t));
         };
-        hi = uint2_t{ pack(h[0], h[1]), pack(h[2], h[3]) };
-        lo = uint2_t{ round2(l[0], l[1]), round2(l[2], l[3]) };
+        float h[4], m[4], l[4];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) { h[r] = cut(p[r]); const float rem = p[r] - h[r]; m[r] = cut(rem); l[r] = rem - m[r]; }
+        part[0] = uint2_t{ pack(h[0], h[1]), pack(h[2], h[3]) };
+        part[1] = uint2_t{ pack(m[0], m[1]), pack(m[2], m[3]) };
+        part[2] = uint2_t{ round2(l[0], l[1]), round2(l[2], l[3]) };
     }
 }
 
@@ -220,16 +227,16 @@ void wkv_prefill_rows(const void* __restrict__ q_, const void* __restrict__ k_, 
         // O[query][column] += sum over keys P[query][key] V[key][column] with the 16-bit matrix
         // instruction (k = 16 keys at once): lane (g, x) supplies k-slots 4g + r, which stand for the
         // keys g + 4r it already holds -- as A operand P[query x][key g + 4r], as B operand
-        // V[key g + 4r][column NE*x + e], the raw cache values.  P goes in as hi + lo.
-        uint2_t pa_hi, pa_lo;
-        split16x4<TT>(p, pa_hi, pa_lo);
+        // V[key g + 4r][column NE*x + e], the raw cache values.  P goes in as a sum of 16-bit parts.
+        uint2_t pa[weight_parts<TT>()];
+        split16x4<TT>(p, pa);
 #pragma unroll
         for (int e = 0; e < NE; ++e) {
             const uint32_t sel = (e & 1) ? 0x07060302u : 0x05040100u;      // high / low halves of two words
             const uint2_t vb = { __builtin_amdgcn_perm(vfrag[1][e >> 1], vfrag[0][e >> 1], sel),
                                  __builtin_amdgcn_perm(vfrag[3][e >> 1], vfrag[2][e >> 1], sel) };
-            o[e] = mfma16<TT>(pa_hi, vb, o[e]);
-            o[e] = mfma16<TT>(pa_lo, vb, o[e]);
+#pragma unroll
+            for (int w = 0; w < weight_parts<TT>(); ++w) o[e] = mfma16<TT>(pa[w], vb, o[e]);
         }
     }
 
