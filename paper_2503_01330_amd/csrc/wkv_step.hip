@@ -80,7 +80,7 @@ namespace {
 // Without it wave 0 does the bookkeeping (~2 us for 411 entries) and then its share of V, and
 // the other waves wait for it at the second barrier.  Chosen by the host (dedicated_wave below).
 template <class TT, int D, int U, int MAXT, bool SEP, bool DED>
-__global__ __launch_bounds__(MAXT)
+__global__ __launch_bounds__(MAXT, 4)
 void wkv_step_kernel(WkvCache c, const void* __restrict__ q_, const void* __restrict__ k_,
                      const void* __restrict__ v_, void* __restrict__ out_, int t)
 {
