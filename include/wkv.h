@@ -59,6 +59,16 @@ extern "C" {
 #define WKV_MERGE_CONVEX     0   /* fold V[j] into its right neighbour (Algorithm 1)                */
 #define WKV_MERGE_NONE       1   /* drop V[j] too: the "Eviction" ablation of Section V-B           */
 
+/* How wkv_step loads the cached K and V rows (wkv_options.streaming).  Every row is read once per
+ * step; whether it is still in the 256 MB last-level cache at the next step depends on how much
+ * else is streamed in between.  AUTO decides at every step: non-temporal loads when the caches of
+ * all live handles on the device together exceed twice that cache (nothing survives until its
+ * next use, and loads that allocate cache lines on their way only cost bandwidth) and a row is at
+ * most 256 bytes; through the caches otherwise.  Results do not depend on the choice. */
+#define WKV_LOADS_AUTO      0
+#define WKV_LOADS_CACHED    1
+#define WKV_LOADS_STREAMING 2
+
 typedef struct wkv_handle wkv_handle;
 
 /* Every field is plain int so the struct can be filled from any language.
@@ -75,7 +85,8 @@ typedef struct wkv_options {
     int threads;                 /* optional: workgroup size 256/512/1024, default chosen by units */
     int split;                   /* optional: workgroups per unit, 1/2/4/8/16; default: 1 unless   */
                                  /*   the units alone would leave most of the GPU idle             */
-    int reserved[4];             /* must be zero                                                   */
+    int streaming;               /* optional: WKV_LOADS_*: how wkv_step loads the cached K/V rows  */
+    int reserved[3];             /* must be zero                                                   */
 } wkv_options;
 
 /*

@@ -25,6 +25,7 @@ WKV_MAX_BUDGET = 4095
 WKV_MAX_PROMPT = 4096
 WKV_SCORE_AVERAGE, WKV_SCORE_CUMULATIVE, WKV_SCORE_LAST = 0, 1, 2
 WKV_MERGE_CONVEX, WKV_MERGE_NONE = 0, 1
+WKV_LOADS_AUTO, WKV_LOADS_CACHED, WKV_LOADS_STREAMING = 0, 1, 2
 (WKV_STEP, WKV_LEN, WKV_K, WKV_V, WKV_SCORE_SUM, WKV_COUNT, WKV_POS, WKV_NMERGED,
  WKV_EVICT_POS, WKV_EVICT_SLOT, WKV_STATUS) = range(11)
 
@@ -35,7 +36,7 @@ EXPORTS = ("wkv_create", "wkv_create_ex", "wkv_step", "wkv_prefill", "wkv_state"
 class wkv_options(C.Structure):
     _fields_ = [(n, C.c_int) for n in ("batch", "heads", "head_dim", "budget", "recent_window",
                                         "dtype", "n_sink", "score_mode", "merge_mode",
-                                        "log_capacity", "threads", "split")] + [("reserved", C.c_int * 4)]
+                                        "log_capacity", "threads", "split", "streaming")] + [("reserved", C.c_int * 3)]
 
 
 class WkvError(RuntimeError):
@@ -77,9 +78,9 @@ def wkv_version() -> int:
 
 
 def make_options(batch, heads, head_dim, budget, recent_window, dtype, n_sink=0, score_mode=0,
-                 merge_mode=0, log_capacity=0, threads=0, split=0) -> wkv_options:
+                 merge_mode=0, log_capacity=0, threads=0, split=0, streaming=0) -> wkv_options:
     return wkv_options(batch, heads, head_dim, budget, recent_window, dtype, n_sink, score_mode,
-                       merge_mode, log_capacity, threads, split)
+                       merge_mode, log_capacity, threads, split, streaming)
 
 
 def wkv_create(batch, heads, head_dim, budget, recent_window, dtype):

@@ -32,8 +32,8 @@ struct WkvCache {
 
 // Launches one decode step for every unit.  t = 0-based index of the incoming
 // token.  threads in {256,512,1024}, with m + 1 <= wkv_step_max_entries(threads).
-// Returns the launch's hipError_t.
-hipError_t wkv_launch_step(const WkvCache& c, int dtype, int head_dim, int threads,
+// stream_loads: cached K/V rows are loaded non-temporally.  Returns the launch's hipError_t.
+hipError_t wkv_launch_step(const WkvCache& c, int dtype, int head_dim, int threads, bool stream_loads,
                            const void* q, const void* k_new, const void* v_new, void* out,
                            int64_t t, hipStream_t stream);
 

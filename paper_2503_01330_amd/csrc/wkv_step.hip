@@ -79,7 +79,7 @@ namespace {
 // other waves (NG - 4 groups), and wave 0 has only the bookkeeping between the two barriers.
 // Without it wave 0 does the bookkeeping (~2 us for 411 entries) and then its share of V, and
 // the other waves wait for it at the second barrier.  Chosen by the host (dedicated_wave below).
-template <class TT, int D, int U, int MAXT, bool SEP, bool DED>
+template <class TT, int D, int U, int MAXT, bool SEP, bool DED, bool STREAM>
 __global__ __launch_bounds__(MAXT, 4)
 void wkv_step_kernel(WkvCache c, const void* __restrict__ q_, const void* __restrict__ k_,
                      const void* __restrict__ v_, void* __restrict__ out_, int t)
@@ -171,7 +171,7 @@ void wkv_step_kernel(WkvCache c, const void* __restrict__ q_, const void* __rest
             int i = base + uu * stride;
             if (i >= Ls) i = dup;
             const char* rp = (!SEP && i == Lc) ? incoming : cached + (size_t)i * ROWB;
-            load_words<NW32>(rp + sub * LANEB, dst[uu]);
+            load_words<NW32, STREAM>(rp + sub * LANEB, dst[uu]);
         }
     };
     auto request = [&](uint32_t (&dst)[U][NW32], const char* cached, const char* incoming, int ch) {
@@ -526,10 +526,14 @@ template <class TT, int D, int U, int MAXT>
 hipError_t prepare_u(size_t lds)
 {
     const void* ks[] = {
-        reinterpret_cast<const void*>(&wkv_step_kernel<TT, D, U, MAXT, false, true>),
-        reinterpret_cast<const void*>(&wkv_step_kernel<TT, D, U, MAXT, true, true>),
-        reinterpret_cast<const void*>(&wkv_step_kernel<TT, D, U, MAXT, false, (MAXT > 512)>),
-        reinterpret_cast<const void*>(&wkv_step_kernel<TT, D, U, MAXT, true, (MAXT > 512)>),
+        reinterpret_cast<const void*>(&wkv_step_kernel<TT, D, U, MAXT, false, true, false>),
+        reinterpret_cast<const void*>(&wkv_step_kernel<TT, D, U, MAXT, true, true, false>),
+        reinterpret_cast<const void*>(&wkv_step_kernel<TT, D, U, MAXT, false, (MAXT > 512), false>),
+        reinterpret_cast<const void*>(&wkv_step_kernel<TT, D, U, MAXT, true, (MAXT > 512), false>),
+        reinterpret_cast<const void*>(&wkv_step_kernel<TT, D, U, MAXT, false, true, true>),
+        reinterpret_cast<const void*>(&wkv_step_kernel<TT, D, U, MAXT, true, true, true>),
+        reinterpret_cast<const void*>(&wkv_step_kernel<TT, D, U, MAXT, false, (MAXT > 512), true>),
+        reinterpret_cast<const void*>(&wkv_step_kernel<TT, D, U, MAXT, true, (MAXT > 512), true>),
     };
     for (const void* k : ks) {
         hipError_t e = hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
@@ -549,32 +553,40 @@ hipError_t prepare(size_t lds)
     return e;
 }
 
-template <class TT, int D, int U, int MAXT, bool DED>
-hipError_t launch_ud(const WkvCache& c, int threads, size_t lds, bool sep, const void* q, const void* k,
-                     const void* v, void* out, int t, hipStream_t stream)
+template <class TT, int D, int U, int MAXT, bool DED, bool STREAM>
+hipError_t launch_uds(const WkvCache& c, int threads, size_t lds, bool sep, const void* q, const void* k,
+                      const void* v, void* out, int t, hipStream_t stream)
 {
     if (sep)
-        hipLaunchKernelGGL((wkv_step_kernel<TT, D, U, MAXT, true, DED>), dim3(c.units), dim3(threads), lds,
+        hipLaunchKernelGGL((wkv_step_kernel<TT, D, U, MAXT, true, DED, STREAM>), dim3(c.units), dim3(threads), lds,
                            stream, c, q, k, v, out, t);
     else
-        hipLaunchKernelGGL((wkv_step_kernel<TT, D, U, MAXT, false, DED>), dim3(c.units), dim3(threads), lds,
+        hipLaunchKernelGGL((wkv_step_kernel<TT, D, U, MAXT, false, DED, STREAM>), dim3(c.units), dim3(threads), lds,
                            stream, c, q, k, v, out, t);
     return hipGetLastError();
 }
 
+template <class TT, int D, int U, int MAXT, bool DED>
+hipError_t launch_ud(const WkvCache& c, int threads, size_t lds, bool sep, bool stream_loads, const void* q,
+                     const void* k, const void* v, void* out, int t, hipStream_t stream)
+{
+    return stream_loads ? launch_uds<TT, D, U, MAXT, DED, true>(c, threads, lds, sep, q, k, v, out, t, stream)
+                        : launch_uds<TT, D, U, MAXT, DED, false>(c, threads, lds, sep, q, k, v, out, t, stream);
+}
+
 template <class TT, int D, int U, int MAXT>
-hipError_t launch_u(const WkvCache& c, int threads, size_t lds, bool sep, const void* q, const void* k,
-                    const void* v, void* out, int t, hipStream_t stream)
+hipError_t launch_u(const WkvCache& c, int threads, size_t lds, bool sep, bool stream_loads, const void* q,
+                    const void* k, const void* v, void* out, int t, hipStream_t stream)
 {
     if constexpr (MAXT <= 512) {
         if (!dedicated_wave(c, threads, (size_t)D * TT::BYTES, U, sep))
-            return launch_ud<TT, D, U, MAXT, false>(c, threads, lds, sep, q, k, v, out, t, stream);
+            return launch_ud<TT, D, U, MAXT, false>(c, threads, lds, sep, stream_loads, q, k, v, out, t, stream);
     }
-    return launch_ud<TT, D, U, MAXT, true>(c, threads, lds, sep, q, k, v, out, t, stream);
+    return launch_ud<TT, D, U, MAXT, true>(c, threads, lds, sep, stream_loads, q, k, v, out, t, stream);
 }
 
 template <class TT, int D, int MAXT>
-hipError_t launch(const WkvCache& c, int threads, size_t lds, const void* q, const void* k,
+hipError_t launch(const WkvCache& c, int threads, size_t lds, bool stream_loads, const void* q, const void* k,
                   const void* v, void* out, int t, hipStream_t stream)
 {
     constexpr int U = unroll<TT, D, MAXT>();
@@ -585,9 +597,9 @@ hipError_t launch(const WkvCache& c, int threads, size_t lds, const void* q, con
         bool sep_half;
         const int slots_half = row_slots(c.m, ng * (U / 2), &sep_half);
         if (slots_half * 10 <= slots * 9)
-            return launch_u<TT, D, U / 2, MAXT>(c, threads, lds, sep_half, q, k, v, out, t, stream);
+            return launch_u<TT, D, U / 2, MAXT>(c, threads, lds, sep_half, stream_loads, q, k, v, out, t, stream);
     }
-    return launch_u<TT, D, U, MAXT>(c, threads, lds, sep, q, k, v, out, t, stream);
+    return launch_u<TT, D, U, MAXT>(c, threads, lds, sep, stream_loads, q, k, v, out, t, stream);
 }
 
 }  // namespace
@@ -612,7 +624,7 @@ hipError_t wkv_step_prepare(int dtype, int head_dim, size_t lds)
     return hipErrorInvalidValue;
 }
 
-hipError_t wkv_launch_step(const WkvCache& c, int dtype, int head_dim, int threads,
+hipError_t wkv_launch_step(const WkvCache& c, int dtype, int head_dim, int threads, bool stream_loads,
                            const void* q, const void* k_new, const void* v_new, void* out,
                            int64_t t, hipStream_t stream)
 {
@@ -620,8 +632,8 @@ hipError_t wkv_launch_step(const WkvCache& c, int dtype, int head_dim, int threa
     const int ti = (int)t;
 #define WKV_CASE(DT, TT, DD) \
     if (dtype == DT && head_dim == DD) return threads > 512 \
-        ? launch<TT, DD, 1024>(c, threads, lds, q, k_new, v_new, out, ti, stream) \
-        : launch<TT, DD, 512>(c, threads, lds, q, k_new, v_new, out, ti, stream);
+        ? launch<TT, DD, 1024>(c, threads, lds, stream_loads, q, k_new, v_new, out, ti, stream) \
+        : launch<TT, DD, 512>(c, threads, lds, stream_loads, q, k_new, v_new, out, ti, stream);
     WKV_CASE(0, TF32, 64)  WKV_CASE(0, TF32, 128)
     WKV_CASE(1, TF16, 64)  WKV_CASE(1, TF16, 128)  WKV_CASE(1, TF16, 256)
     WKV_CASE(2, TBF16, 64) WKV_CASE(2, TBF16, 128) WKV_CASE(2, TBF16, 256)

@@ -42,7 +42,7 @@ def test_options_struct_layout():
     (dict(score_mode=3), wkv.WKV_EINVAL), (dict(merge_mode=2), wkv.WKV_EINVAL),
     (dict(score_mode=1, merge_mode=0), wkv.WKV_EINVAL), (dict(threads=128), wkv.WKV_EINVAL),
     (dict(log_capacity=-5), wkv.WKV_EINVAL), (dict(split=3), wkv.WKV_EINVAL), (dict(split=32), wkv.WKV_EINVAL),
-    (dict(split=-1), wkv.WKV_EINVAL),
+    (dict(split=-1), wkv.WKV_EINVAL), (dict(streaming=3), wkv.WKV_EINVAL), (dict(streaming=-1), wkv.WKV_EINVAL),
 ])
 def test_invalid_options_are_rejected_before_touching_the_gpu(kw, code):
     base = dict(batch=1, heads=4, head_dim=64, budget=64, recent_window=16, dtype=wkv.WKV_FP32)

@@ -151,6 +151,27 @@ def test_sink_protection_and_eviction_variants():
     _run(cfg, merge_mode=wkv.WKV_MERGE_NONE, score_mode=wkv.WKV_SCORE_LAST)
 
 
+@pytest.mark.parametrize("dtype,d,m,threads", [("fp16", 128, 410, 0), ("bf16", 64, 300, 256), ("fp32", 64, 130, 512),
+                                                ("bf16", 256, 96, 0), ("fp32", 128, 128, 1024), ("fp16", 64, 256, 512)])
+def test_streaming_loads_change_nothing(dtype, d, m, threads):
+    """The cached rows loaded through the caches and non-temporally (the library chooses by the
+    amount of live cache; here both are forced): outputs, eviction log and state bit-identical, and
+    the non-temporal run against the oracle."""
+    cfg = synth.StreamConfig(f"nt-{dtype}-{d}", 7300 + d + m, 2, 5, d, dtype, m + 40, m, 6)
+    kw = dict(threads=threads) if threads else {}
+    a = parity.gpu_stream(cfg, streaming=wkv.WKV_LOADS_CACHED, **kw)
+    b = parity.gpu_stream(cfg, streaming=wkv.WKV_LOADS_STREAMING, **kw)
+    try:
+        assert np.array_equal(a["out"], b["out"])
+        assert np.array_equal(a["evict_pos"], b["evict_pos"]) and np.array_equal(a["evict_slot"], b["evict_slot"])
+        for what in (wkv.WKV_K, wkv.WKV_V, wkv.WKV_SCORE_SUM, wkv.WKV_POS):
+            assert np.array_equal(a["cache"].state(what), b["cache"].state(what)), what
+        stats = parity.compare(cfg, b)
+        assert stats["near_ties"] == 0
+    finally:
+        a["cache"].close(); b["cache"].close()
+
+
 def test_determinism_same_stream_twice():
     cfg = synth.scaled(synth.CONFIGS["cfg2"], steps=1100, heads=8, budget=300)
     a = parity.gpu_stream(cfg); b = parity.gpu_stream(cfg)
