@@ -269,8 +269,8 @@ int wkv_step(wkv_handle* h, const void* q, const void* k_new, const void* v_new,
     if (e != hipSuccess) return fail(WKV_EHIP, "hipGetDevice: %s", hipGetErrorString(e));
     if (dev != h->device) return fail(WKV_EINVAL, "handle belongs to device %d, current device is %d", h->device, dev);
     e = h->sp.S > 1
-        ? wkv_launch_split(h->c, h->sp, h->opt.dtype, h->opt.head_dim, h->threads, q, k_new, v_new, out, h->t,
-                           (hipStream_t)stream)
+        ? wkv_launch_split(h->c, h->sp, h->opt.dtype, h->opt.head_dim, h->threads, stream_loads(h->opt, h->device),
+                           q, k_new, v_new, out, h->t, (hipStream_t)stream)
         : wkv_launch_step(h->c, h->opt.dtype, h->opt.head_dim, h->threads, stream_loads(h->opt, h->device),
                           q, k_new, v_new, out, h->t, (hipStream_t)stream);
     if (e != hipSuccess) return fail(WKV_EHIP, "kernel launch: %s", hipGetErrorString(e));

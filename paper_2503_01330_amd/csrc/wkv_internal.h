@@ -63,7 +63,7 @@ struct WkvSplit {
 
 // Same contract as wkv_launch_step, grid = units * sp.S workgroups.
 hipError_t wkv_launch_split(const WkvCache& c, const WkvSplit& sp, int dtype, int head_dim, int threads,
-                            const void* q, const void* k_new, const void* v_new, void* out,
+                            bool stream_loads, const void* q, const void* k_new, const void* v_new, void* out,
                             int64_t t, hipStream_t stream);
 size_t wkv_split_lds_bytes(int m, int dtype, int head_dim, int threads);
 hipError_t wkv_split_prepare(int dtype, int head_dim, size_t lds);

@@ -31,7 +31,7 @@
 
 namespace {
 
-template <class TT, int D, int U, int MAXT>
+template <class TT, int D, int U, int MAXT, bool STREAM>
 __global__ __launch_bounds__(MAXT)
 void wkv_split_kernel(WkvCache c, WkvSplit sp, const void* __restrict__ q_, const void* __restrict__ k_,
                       const void* __restrict__ v_, void* __restrict__ out_, int t)
@@ -100,7 +100,7 @@ void wkv_split_kernel(WkvCache c, WkvSplit sp, const void* __restrict__ q_, cons
             int i = base + uu * NG;
             if (i >= hi) i = dup;
             const char* rp = (i == Lc) ? incoming : cached + (size_t)i * ROWB;
-            load_words<NW32>(rp + sub * LANEB, dst[uu]);
+            load_words<NW32, STREAM>(rp + sub * LANEB, dst[uu]);
         }
     };
     request(kw, Kc, ku, 0);
@@ -388,16 +388,23 @@ void wkv_split_kernel(WkvCache c, WkvSplit sp, const void* __restrict__ q_, cons
 template <class TT, int D, int MAXT>
 hipError_t prepare(size_t lds)
 {
-    return hipFuncSetAttribute(reinterpret_cast<const void*>(&wkv_split_kernel<TT, D, unroll<TT, D, MAXT>(), MAXT>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&wkv_split_kernel<TT, D, unroll<TT, D, MAXT>(), MAXT, false>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    return hipFuncSetAttribute(reinterpret_cast<const void*>(&wkv_split_kernel<TT, D, unroll<TT, D, MAXT>(), MAXT, true>),
                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
 }
 
 template <class TT, int D, int MAXT>
-hipError_t launch(const WkvCache& c, const WkvSplit& sp, int threads, size_t lds, const void* q, const void* k,
-                  const void* v, void* out, int t, hipStream_t stream)
+hipError_t launch(const WkvCache& c, const WkvSplit& sp, int threads, size_t lds, bool stream_loads, const void* q,
+                  const void* k, const void* v, void* out, int t, hipStream_t stream)
 {
-    hipLaunchKernelGGL((wkv_split_kernel<TT, D, unroll<TT, D, MAXT>(), MAXT>), dim3(c.units * sp.S), dim3(threads),
-                       lds, stream, c, sp, q, k, v, out, t);
+    if (stream_loads)
+        hipLaunchKernelGGL((wkv_split_kernel<TT, D, unroll<TT, D, MAXT>(), MAXT, true>), dim3(c.units * sp.S),
+                           dim3(threads), lds, stream, c, sp, q, k, v, out, t);
+    else
+        hipLaunchKernelGGL((wkv_split_kernel<TT, D, unroll<TT, D, MAXT>(), MAXT, false>), dim3(c.units * sp.S),
+                           dim3(threads), lds, stream, c, sp, q, k, v, out, t);
     return hipGetLastError();
 }
 
@@ -422,15 +429,15 @@ hipError_t wkv_split_prepare(int dtype, int head_dim, size_t lds)
 }
 
 hipError_t wkv_launch_split(const WkvCache& c, const WkvSplit& sp, int dtype, int head_dim, int threads,
-                            const void* q, const void* k_new, const void* v_new, void* out,
+                            bool stream_loads, const void* q, const void* k_new, const void* v_new, void* out,
                             int64_t t, hipStream_t stream)
 {
     const size_t lds = wkv_split_lds_bytes(c.m, dtype, head_dim, threads);
     const int ti = (int)t;
 #define WKV_CASE(DT, TT, DD) \
     if (dtype == DT && head_dim == DD) return threads > 512 \
-        ? launch<TT, DD, 1024>(c, sp, threads, lds, q, k_new, v_new, out, ti, stream) \
-        : launch<TT, DD, 512>(c, sp, threads, lds, q, k_new, v_new, out, ti, stream);
+        ? launch<TT, DD, 1024>(c, sp, threads, lds, stream_loads, q, k_new, v_new, out, ti, stream) \
+        : launch<TT, DD, 512>(c, sp, threads, lds, stream_loads, q, k_new, v_new, out, ti, stream);
     WKV_CASE(0, TF32, 64)  WKV_CASE(0, TF32, 128)
     WKV_CASE(1, TF16, 64)  WKV_CASE(1, TF16, 128)  WKV_CASE(1, TF16, 256)
     WKV_CASE(2, TBF16, 64) WKV_CASE(2, TBF16, 128) WKV_CASE(2, TBF16, 256)

@@ -151,14 +151,17 @@ def test_sink_protection_and_eviction_variants():
     _run(cfg, merge_mode=wkv.WKV_MERGE_NONE, score_mode=wkv.WKV_SCORE_LAST)
 
 
-@pytest.mark.parametrize("dtype,d,m,threads", [("fp16", 128, 410, 0), ("bf16", 64, 300, 256), ("fp32", 64, 130, 512),
-                                                ("bf16", 256, 96, 0), ("fp32", 128, 128, 1024), ("fp16", 64, 256, 512)])
-def test_streaming_loads_change_nothing(dtype, d, m, threads):
+@pytest.mark.parametrize("dtype,d,m,threads,split", [
+    ("fp16", 128, 410, 0, 1), ("bf16", 64, 300, 256, 1), ("fp32", 64, 130, 512, 1), ("bf16", 256, 96, 0, 1),
+    ("fp32", 128, 128, 1024, 1), ("fp16", 64, 256, 512, 1), ("fp16", 128, 700, 0, 4), ("bf16", 64, 333, 1024, 2)])
+def test_streaming_loads_change_nothing(dtype, d, m, threads, split):
     """The cached rows loaded through the caches and non-temporally (the library chooses by the
     amount of live cache; here both are forced): outputs, eviction log and state bit-identical, and
     the non-temporal run against the oracle."""
     cfg = synth.StreamConfig(f"nt-{dtype}-{d}", 7300 + d + m, 2, 5, d, dtype, m + 40, m, 6)
-    kw = dict(threads=threads) if threads else {}
+    kw = dict(split=split)
+    if threads:
+        kw["threads"] = threads
     a = parity.gpu_stream(cfg, streaming=wkv.WKV_LOADS_CACHED, **kw)
     b = parity.gpu_stream(cfg, streaming=wkv.WKV_LOADS_STREAMING, **kw)
     try:
