@@ -107,6 +107,14 @@ int validate(const wkv_options& o, int* threads, int* split)
         // units), except for 128-byte rows, where 256 threads are 20 % ahead; slices: 512
         const int row_bytes = o.head_dim * dtype_bytes(o.dtype);
         th = sp > 1 ? 512 : units >= 1024 ? (row_bytes < 256 ? 256 : 512) : units > 256 ? 512 : 1024;
+        // from 768 units on, 256 threads where their finer chunks leave clearly fewer padded row
+        // requests (m = 410: 448 instead of 512): 768 x 410 33.4 -> 29.5 us, 1024 x 410 42.6 -> 37.7,
+        // 1024 x 520 50.8 -> 47.0, 2048 x 410 81.2 -> 78.1; with equal padding (m = 512) 512 threads
+        // stay 0.3-2.5 % ahead; below 768 units they win either way
+        if (sp == 1 && units >= 768 && row_bytes == 256 && th == 512 && fits(256) &&
+            wkv_step_padded_rows(o.budget, o.dtype, o.head_dim, 256) * 20 <=
+            wkv_step_padded_rows(o.budget, o.dtype, o.head_dim, 512) * 19)
+            th = 256;
         while (th < 1024 && !fits(th)) th *= 2;
     }
     if (th != 256 && th != 512 && th != 1024) return fail(WKV_EINVAL, "threads must be 256, 512 or 1024");

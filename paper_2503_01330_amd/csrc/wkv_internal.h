@@ -37,6 +37,10 @@ hipError_t wkv_launch_step(const WkvCache& c, int dtype, int head_dim, int threa
                            const void* q, const void* k_new, const void* v_new, void* out,
                            int64_t t, hipStream_t stream);
 
+// Row requests per matrix, group and step that wkv_launch_step issues for a budget of m slots,
+// padding of the last chunk included (the chunk depth it would choose is taken into account).
+int wkv_step_padded_rows(int m, int dtype, int head_dim, int threads);
+
 // Bytes of dynamic LDS wkv_launch_step needs for this shape.
 size_t wkv_step_lds_bytes(int m, int dtype, int head_dim, int threads);
 

@@ -613,6 +613,32 @@ size_t wkv_step_lds_bytes(int m, int dtype, int head_dim, int threads)
 
 int wkv_step_max_entries(int threads) { return MAXPT * threads; }
 
+namespace {
+template <class TT, int D, int MAXT> int padded_rows(int m, int threads)
+{
+    constexpr int U = unroll<TT, D, MAXT>();
+    const int ng = threads / ROW_LANES;
+    bool sep;
+    int slots = row_slots(m, ng * U, &sep);
+    if constexpr (has_half_chunk<TT, D, MAXT>()) {
+        const int slots_half = row_slots(m, ng * (U / 2), &sep);
+        if (slots_half * 10 <= slots * 9) slots = slots_half;
+    }
+    return slots;
+}
+}  // namespace
+
+int wkv_step_padded_rows(int m, int dtype, int head_dim, int threads)
+{
+#define WKV_CASE(DT, TT, DD) \
+    if (dtype == DT && head_dim == DD) return threads > 512 ? padded_rows<TT, DD, 1024>(m, threads) : padded_rows<TT, DD, 512>(m, threads);
+    WKV_CASE(0, TF32, 64)  WKV_CASE(0, TF32, 128)
+    WKV_CASE(1, TF16, 64)  WKV_CASE(1, TF16, 128)  WKV_CASE(1, TF16, 256)
+    WKV_CASE(2, TBF16, 64) WKV_CASE(2, TBF16, 128) WKV_CASE(2, TBF16, 256)
+#undef WKV_CASE
+    return 0;
+}
+
 hipError_t wkv_step_prepare(int dtype, int head_dim, size_t lds)
 {
 #define WKV_CASE(DT, TT, DD) if (dtype == DT && head_dim == DD) { \
