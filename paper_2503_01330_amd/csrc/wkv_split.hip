@@ -169,6 +169,10 @@ void wkv_split_kernel(WkvCache c, WkvSplit sp, const void* __restrict__ q_, cons
         for (int uu = 0; uu < U; ++uu) {
             const int i = base + uu * NG;
             const S p = (i < hi) ? soft_exp((S)(sl[(i < hi) ? i - lo : 0] - Ms)) : (S)0;
+            // touched here and not before: left alone, the compiler converts the first V rows right
+            // behind their request, i.e. waits for them ahead of the barrier (see wkv_step.hip)
+#pragma unroll
+            for (int w = 0; w < NW32; ++w) asm volatile("" : "+v"(vw[uu][w]));
             float vx[EPL];
             decode<TT, EPL, NW32>(vw[uu], vx);
             l_run += p;

@@ -166,13 +166,18 @@ void wkv_step_kernel(WkvCache c, const void* __restrict__ q_, const void* __rest
     uint32_t kw[U][NW32], vw[U][NW32];
     auto request_rows = [&](uint32_t (&dst)[U][NW32], const char* cached, const char* incoming, int base, int stride) {
         const int dup = (base < Ls) ? base : 0;            // where out-of-range groups point (harmless duplicate)
+        // all addresses first, then the loads back to back: computed in between, an address may be
+        // given a register that an earlier load of the batch is still going to write, and the
+        // compiler then waits for that load -- a whole memory round trip -- before it goes on
+        const char* rp[U];
 #pragma unroll
         for (int uu = 0; uu < U; ++uu) {
             int i = base + uu * stride;
             if (i >= Ls) i = dup;
-            const char* rp = (!SEP && i == Lc) ? incoming : cached + (size_t)i * ROWB;
-            load_words<NW32, STREAM>(rp + sub * LANEB, dst[uu]);
+            rp[uu] = ((!SEP && i == Lc) ? incoming : cached + (size_t)i * ROWB) + sub * LANEB;
         }
+#pragma unroll
+        for (int uu = 0; uu < U; ++uu) load_words<NW32, STREAM>(rp[uu], dst[uu]);
     };
     auto request = [&](uint32_t (&dst)[U][NW32], const char* cached, const char* incoming, int ch) {
         request_rows(dst, cached, incoming, ch * CH + gid, NG);
@@ -367,6 +372,11 @@ void wkv_step_kernel(WkvCache c, const void* __restrict__ q_, const void* __rest
         for (int uu = 0; uu < U; ++uu) {
             const int i = base + uu * NGv;
             const S p = (i < Ls) ? soft_exp((S)(sl[(i < Ls) ? i : 0] - Mx)) : (S)0;
+            // The row is touched here and not before: left alone, the compiler converts the first V
+            // rows right behind their request, ahead of the first barrier, and every wave then
+            // waits for its V rows before the bookkeeping can even start.
+#pragma unroll
+            for (int w = 0; w < NW32; ++w) asm volatile("" : "+v"(vw[uu][w]));
             float vx[EPL];
             decode<TT, EPL, NW32>(vw[uu], vx);
             l_run += p;
