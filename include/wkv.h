@@ -170,7 +170,9 @@ int wkv_prefill(wkv_handle* h, const void* q, const void* k, const void* v, void
  * device memory.  For the two eviction logs, n = bytes / (4*units) most recent
  * steps are returned, oldest first; n must not exceed min(tokens, log_capacity).
  * For everything else `bytes` must be at least the size listed above
- * (WKV_ESIZE otherwise; nothing is written then).
+ * (WKV_ESIZE otherwise; nothing is written then).  Like every call that takes a handle, it
+ * must come with the handle's device current (WKV_EINVAL otherwise); wkv_destroy alone does
+ * not mind.
  */
 int wkv_state(wkv_handle* h, int what, void* host_dst, size_t bytes);
 
@@ -182,7 +184,8 @@ int wkv_state(wkv_handle* h, int what, void* host_dst, size_t bytes);
  *   K, V   : dtype[units,len,d];  score_sum : double[units,len];  pos : int32[units,len],
  *            strictly increasing within a unit, last entry = tokens-1, all < tokens
  * Counts and merge counts follow from pos and are not passed.  Synchronous; waits for
- * enqueued work first.  The eviction log is cleared.  On error the cache is unchanged.
+ * enqueued work first.  The eviction log is cleared.  On error the cache is unchanged, except for
+ * WKV_EHIP during the upload itself (the message says so).
  */
 int wkv_load(wkv_handle* h, int64_t tokens, int len, const void* K, const void* V,
              const double* score_sum, const int32_t* pos);

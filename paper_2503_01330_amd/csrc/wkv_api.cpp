@@ -158,6 +158,20 @@ struct wkv_handle {
     int64_t log_from; // first step whose eviction log entry is valid (after wkv_load)
 };
 
+namespace {
+
+// The handle's memory and the kernels' attributes belong to one device; calls come from it.
+int on_device(const wkv_handle* h)
+{
+    int dev;
+    const hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return fail(WKV_EHIP, "hipGetDevice: %s", hipGetErrorString(e));
+    if (dev != h->device) return fail(WKV_EINVAL, "handle belongs to device %d, current device is %d", h->device, dev);
+    return WKV_OK;
+}
+
+}  // namespace
+
 extern "C" {
 
 const char* wkv_last_error(void) { return g_err.c_str(); }
@@ -272,11 +286,9 @@ int wkv_step(wkv_handle* h, const void* q, const void* k_new, const void* v_new,
     if ((((uintptr_t)q | (uintptr_t)k_new | (uintptr_t)v_new | (uintptr_t)out) & 15) != 0)
         return fail(WKV_EINVAL, "q, k_new, v_new and out must be 16-byte aligned");
     if (h->t >= 0x7FFFFFF0LL) return fail(WKV_ESIZE, "token counter would overflow");
-    int dev;
-    hipError_t e = hipGetDevice(&dev);
-    if (e != hipSuccess) return fail(WKV_EHIP, "hipGetDevice: %s", hipGetErrorString(e));
-    if (dev != h->device) return fail(WKV_EINVAL, "handle belongs to device %d, current device is %d", h->device, dev);
-    e = h->sp.S > 1
+    const int rc = on_device(h);
+    if (rc != WKV_OK) return rc;
+    const hipError_t e = h->sp.S > 1
         ? wkv_launch_split(h->c, h->sp, h->opt.dtype, h->opt.head_dim, h->threads, stream_loads(h->opt, h->device),
                            q, k_new, v_new, out, h->t, (hipStream_t)stream)
         : wkv_launch_step(h->c, h->opt.dtype, h->opt.head_dim, h->threads, stream_loads(h->opt, h->device),
@@ -301,12 +313,10 @@ int wkv_prefill(wkv_handle* h, const void* q, const void* k, const void* v, void
         return fail(WKV_ESIZE, "wkv_prefill is built for 16-bit caches with head_dim 64 or 128");
     if (o.score_mode == WKV_SCORE_LAST)
         return fail(WKV_EINVAL, "the last-step scoring rule is not defined for a prompt");
-    int dev;
-    hipError_t e = hipGetDevice(&dev);
-    if (e != hipSuccess) return fail(WKV_EHIP, "hipGetDevice: %s", hipGetErrorString(e));
-    if (dev != h->device) return fail(WKV_EINVAL, "handle belongs to device %d, current device is %d", h->device, dev);
+    const int rc = on_device(h);
+    if (rc != WKV_OK) return rc;
     int lds_max = 0;
-    e = hipDeviceGetAttribute(&lds_max, hipDeviceAttributeMaxSharedMemoryPerBlock, h->device);
+    hipError_t e = hipDeviceGetAttribute(&lds_max, hipDeviceAttributeMaxSharedMemoryPerBlock, h->device);
     if (e == hipSuccess && wkv_prefill_lds_bytes(n_tokens) > (size_t)lds_max)
         return fail(WKV_ESIZE, "a prompt of %d tokens needs %zu bytes of LDS, the device offers %d", n_tokens,
                     wkv_prefill_lds_bytes(n_tokens), lds_max);
@@ -331,9 +341,8 @@ int wkv_prefill(wkv_handle* h, const void* q, const void* k, const void* v, void
     return WKV_OK;
 }
 
-int wkv_state(wkv_handle* h, int what, void* dst, size_t bytes)
+static int state_impl(wkv_handle* h, int what, void* dst, size_t bytes)
 {
-    if (!h || !dst) return fail(WKV_EINVAL, "null argument");
     const WkvCache& c = h->c;
     const size_t units = c.units, cap = c.m;
     const int64_t T = h->t;
@@ -349,6 +358,8 @@ int wkv_state(wkv_handle* h, int what, void* dst, size_t bytes)
         memcpy(dst, &l, sizeof l);
         return WKV_OK;
     }
+    int rc = on_device(h);
+    if (rc != WKV_OK) return rc;
     hipError_t e = hipDeviceSynchronize();
     if (e != hipSuccess) return fail(WKV_EHIP, "hipDeviceSynchronize: %s", hipGetErrorString(e));
 
@@ -441,10 +452,19 @@ int wkv_state(wkv_handle* h, int what, void* dst, size_t bytes)
     return fail(WKV_EINVAL, "unknown state item %d", what);
 }
 
-int wkv_load(wkv_handle* h, int64_t tokens, int len, const void* K, const void* V,
-             const double* score_sum, const int32_t* pos)
+int wkv_state(wkv_handle* h, int what, void* dst, size_t bytes)
 {
-    if (!h) return fail(WKV_EINVAL, "null handle");
+    if (!h || !dst) return fail(WKV_EINVAL, "null argument");
+    try {
+        return state_impl(h, what, dst, bytes);
+    } catch (const std::bad_alloc&) {
+        return fail(WKV_ENOMEM, "host allocation failed");
+    }
+}
+
+static int load_impl(wkv_handle* h, int64_t tokens, int len, const void* K, const void* V,
+                     const double* score_sum, const int32_t* pos)
+{
     WkvCache& c = h->c;
     const size_t units = c.units, m = c.m;
     if (tokens < 0 || tokens >= 0x7FFFFFF0LL) return fail(WKV_EINVAL, "tokens out of range");
@@ -457,6 +477,8 @@ int wkv_load(wkv_handle* h, int64_t tokens, int len, const void* K, const void* 
                 return fail(WKV_EINVAL, "pos of unit %zu is not strictly increasing within [0, tokens)", u);
         if (pu[len - 1] != tokens - 1) return fail(WKV_EINVAL, "the newest token must be retained (unit %zu)", u);
     }
+    int rc = on_device(h);
+    if (rc != WKV_OK) return rc;
     hipError_t e = hipDeviceSynchronize();
     if (e != hipSuccess) return fail(WKV_EHIP, "hipDeviceSynchronize: %s", hipGetErrorString(e));
     // device layout: slot l of a unit holds the l-th token in token order, links run l -> l+1
@@ -485,15 +507,30 @@ int wkv_load(wkv_handle* h, int64_t tokens, int len, const void* K, const void* 
     return WKV_OK;
 }
 
+int wkv_load(wkv_handle* h, int64_t tokens, int len, const void* K, const void* V,
+             const double* score_sum, const int32_t* pos)
+{
+    if (!h) return fail(WKV_EINVAL, "null handle");
+    try {
+        return load_impl(h, tokens, len, K, V, score_sum, pos);
+    } catch (const std::bad_alloc&) {
+        return fail(WKV_ENOMEM, "host allocation failed");
+    }
+}
+
 int wkv_destroy(wkv_handle* h)
 {
     if (!h) return WKV_OK;
+    // wait for the handle's device, whichever is current
+    int cur = -1;
+    const bool moved = hipGetDevice(&cur) == hipSuccess && cur != h->device && hipSetDevice(h->device) == hipSuccess;
     (void)hipDeviceSynchronize();
     WkvCache& c = h->c;
     void* bufs[] = { c.K, c.V, c.a, c.pos, c.nxt, c.log_pos, c.log_slot, c.status,
                      h->sp.lg, h->sp.po, h->sp.pm, h->sp.pl, h->sp.pe, h->sp.cnt };
     for (void* b : bufs) if (b) (void)hipFree(b);
     count_live(h->device, -2 * (long long)sizes(h->opt, h->sp.S).kv);
+    if (moved) (void)hipSetDevice(cur);
     delete h;
     return WKV_OK;
 }
