@@ -119,6 +119,30 @@ template <class TT> __device__ __forceinline__ float4_t mfma16(uint2_t a, uint2_
         return __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(short4_t, a), __builtin_bit_cast(short4_t, b), c, 0, 0, 0);
 }
 
+// exp(x) for the arguments a softmax produces: x <= 0 (a rounding error above 0 is fine), -inf
+// included.  x = (64 n + j + f) ln2 / 64 with integers n, 0 <= j < 64 and |f| <= 1/2:
+// exp(x) = 2^n . 2^(j/64) . exp(f ln2 / 64); the middle factor comes from a 64-entry table in LDS,
+// the last one from the Taylor quartic (remainder below r^5 / 120 < 4e-14 for |r| <= ln2 / 128), the
+// first is applied by ldexp, which also takes care of gradual underflow.  Relative error about
+// 1e-13 -- eight orders below what separates two scores that may legitimately be ranked either
+// way -- at ten double-precision instructions, against the library routine's two dozen; on this
+// part they do not overlap with the fp64 matrix instruction, so they count in full.
+__device__ __forceinline__ void exp_table_init(double* tab) {
+    if (threadIdx.x < 64) tab[threadIdx.x] = exp2((double)threadIdx.x * (1.0 / 64.0));
+    __syncthreads();
+}
+__device__ __forceinline__ double exp_nonpos(double x, const double* tab) {
+    const double xc = (x < -750.0) ? -750.0 : x;                         // exp(-750) = 0 in fp64; keeps n in range; NaN stays NaN
+    const double kd = __builtin_rint(xc * 92.332482616893656877);        // 64 / ln 2
+    const double r = fma(kd, -0.010830424696249145, xc);                 // ln 2 / 64
+    const int k = (int)kd;
+    const double tj = tab[k & 63];
+    double p = fma(r, 1.0 / 24.0, 1.0 / 6.0);
+    p = fma(p, r, 0.5);
+    p = fma(p, r, 1.0);
+    p = fma(p, r, 1.0);
+    return ldexp(tj * p, k >> 6);
+}
 
 // S^T tile: rows = 16 keys, columns = 16 queries; register r of lane (g, x) = key g + 4r, query x.
 // Both operands are the exact storage values; the softmax scale is applied to the four results.
@@ -152,6 +176,8 @@ void wkv_prefill_rows(const void* __restrict__ q_, const void* __restrict__ k_, 
     const int groups = (ntiles + 3) / 4;
     const int u = xcd_unit(blockIdx.x, groups);
     const int qt = (groups - 1 - (int)((blockIdx.x >> 3) % groups)) * 4 + wid;   // long rows are scheduled first
+    __shared__ double etab[64];
+    exp_table_init(etab);                     // every wave of the workgroup: ahead of the early exit
     if (u >= units || qt >= ntiles) return;
     const size_t tok = (size_t)units * ROWB;                              // bytes from one token to the next
     const char* qb = reinterpret_cast<const char*>(q_) + (size_t)u * ROWB;
@@ -207,7 +233,7 @@ void wkv_prefill_rows(const void* __restrict__ q_, const void* __restrict__ k_, 
         // tiles of a row it rarely moves: the rescaling (an exp, the running sum and all output
         // accumulators of the wave) is skipped unless some query of the tile needs it.
         if (__any(mnew > mrow)) {
-            const double resc = exp(mrow - mnew);             // 0 on the first tile (mrow = -inf), 1 where nothing moved
+            const double resc = exp_nonpos(mrow - mnew, etab);             // 0 on the first tile (mrow = -inf), 1 where nothing moved
             lrow *= resc;
             mrow = mnew;
             const float rf = (float)resc;                     // the output rows this lane holds (queries 4g + r') by their own factor
@@ -221,7 +247,7 @@ void wkv_prefill_rows(const void* __restrict__ q_, const void* __restrict__ k_, 
         float p[4];
         double psum = 0.0;
 #pragma unroll
-        for (int r = 0; r < 4; ++r) { const double e = exp(s[r] - mrow); psum += e; p[r] = (float)e; }
+        for (int r = 0; r < 4; ++r) { const double e = exp_nonpos(s[r] - mrow, etab); psum += e; p[r] = (float)e; }
         psum = rows_sum(psum);
         lrow += psum;
         // O[query][column] += sum over keys P[query][key] V[key][column] with the 16-bit matrix
@@ -270,6 +296,8 @@ void wkv_prefill_scores(const void* __restrict__ q_, const void* __restrict__ k_
     const int groups = (ntiles + 3) / 4;
     const int u = xcd_unit(blockIdx.x, groups);
     const int kt = (int)((blockIdx.x >> 3) % groups) * 4 + wid;           // low key tiles have the most rows: first
+    __shared__ double etab[64];
+    exp_table_init(etab);                     // every wave of the workgroup: ahead of the early exit
     if (u >= units || kt >= ntiles) return;
     const size_t tok = (size_t)units * ROWB;
     const char* qb = reinterpret_cast<const char*>(q_) + (size_t)u * ROWB;
@@ -322,7 +350,7 @@ void wkv_prefill_scores(const void* __restrict__ q_, const void* __restrict__ k_
         for (int r = 0; r < 4; ++r) {
             const int key = kt * TILE + g + 4 * r;
             const bool on = tq < P && key <= tq;                           // causal, and inside the prompt
-            acc[r] += exp(on ? s_cur[r] - l_cur : -INFINITY);              // exp(-inf) = 0; no branch
+            acc[r] += exp_nonpos(on ? s_cur[r] - l_cur : -INFINITY, etab);  // exp(-inf) = 0; no branch
         }
         s_cur = s_next;
         l_cur = l_next;
