@@ -359,6 +359,47 @@ def test_two_handles_on_two_streams_do_not_interfere():
     runs[1]["cache"].close()
 
 
+def test_a_nan_in_one_unit_is_flagged_and_stays_in_that_unit():
+    """A NaN in one unit's query at one step: the status counter of non-finite scores goes up,
+    that unit's output of the step is NaN, and every other unit -- outputs, evictions, cache --
+    is bit for bit what the clean stream gives (units never interact, Section III-A)."""
+    cfg = synth.StreamConfig("nf", 7700, 1, 4, 64, "fp16", 120, 40, 8)
+    q, k, v = synth.Stream(cfg).steps(0, cfg.steps)
+
+    def run(qa):
+        tq, tk, tv = (parity.to_device(x, cfg.dtype) for x in (qa, k, v))
+        out = torch.empty_like(tq)
+        cache = wkv.Cache(cfg.batch, cfg.heads, cfg.head_dim, cfg.budget, cfg.recent,
+                          synth.DTYPE_CODE[cfg.dtype], split=1)
+        try:
+            for t in range(cfg.steps):
+                cache.step(tq[t], tk[t], tv[t], out[t])
+            torch.cuda.synchronize()
+            pos, slot = cache.evictions(cfg.steps)
+            return dict(out=out.cpu().numpy().reshape(cfg.steps, cfg.units, cfg.head_dim), pos=pos, slot=slot,
+                        K=cache.state(wkv.WKV_K), V=cache.state(wkv.WKV_V), a=cache.state(wkv.WKV_SCORE_SUM),
+                        status=cache.state(wkv.WKV_STATUS))
+        finally:
+            cache.close()
+
+    clean = run(q)
+    bad_q = q.copy()
+    bad_q[50, 1, 3] = np.nan                 # token 50, unit 1
+    dirty = run(bad_q)
+    assert list(clean["status"]) == [0, 0]
+    assert dirty["status"][1] > 0
+    assert np.isnan(dirty["out"][50, 1]).all()
+    others = [0, 2, 3]
+    assert np.array_equal(dirty["out"][:, others].view(np.uint16), clean["out"][:, others].view(np.uint16))
+    assert np.array_equal(dirty["pos"][:, others], clean["pos"][:, others])
+    assert np.array_equal(dirty["slot"][:, others], clean["slot"][:, others])
+    for item in ("K", "V"):
+        assert np.array_equal(dirty[item][others].view(np.uint16), clean[item][others].view(np.uint16))
+    assert np.array_equal(dirty["a"][others], clean["a"][others])
+    # the unit concerned keeps evicting one token per step (its scores rank as +inf, oldest first)
+    assert (dirty["pos"][cfg.budget:, 1] >= 0).all()
+
+
 def test_checkpoint_and_resume():
     """State read back with wkv_state and loaded into a fresh handle continues with the same
     evictions and retained keys.  A loaded cache sits in token order in memory, the original does

@@ -141,6 +141,41 @@ def test_outputs_may_be_skipped():
         g["cache"].close()
 
 
+def test_a_nan_in_one_unit_of_the_prompt_is_flagged_and_stays_in_that_unit():
+    """A NaN in one unit's query of one prompt token: non-finite scores are counted in the status,
+    that row's output is NaN, and the other units' outputs and compressed caches are bit for bit
+    those of the clean prompt (units never interact, Section III-A)."""
+    cfg = synth.StreamConfig("pre-nf", 8600, 1, 3, 64, "fp16", 150, 40, 8)
+    P = 150
+    q, k, v = (synth.storage_to_f32(x, cfg.dtype) for x in synth.Stream(cfg).steps(0, P))
+    shape = (P, cfg.units, cfg.head_dim)
+
+    def run(qa):
+        g = parity.gpu_prefill(cfg, P, arrays=(qa.reshape(shape), k.reshape(shape), v.reshape(shape)))
+        c = g["cache"]
+        try:
+            return dict(out=g["out"], K=c.state(wkv.WKV_K), V=c.state(wkv.WKV_V), a=c.state(wkv.WKV_SCORE_SUM),
+                        pos=c.state(wkv.WKV_POS), status=c.state(wkv.WKV_STATUS))
+        finally:
+            c.close()
+
+    clean = run(q)
+    bad_q = q.copy().reshape(shape)
+    bad_q[60, 1, 5] = np.nan
+    dirty = run(bad_q)
+    assert list(clean["status"]) == [0, 0]
+    assert dirty["status"][1] > 0
+    assert np.isnan(dirty["out"][60, 1]).all()
+    others = [0, 2]
+    assert np.array_equal(dirty["out"][:, others], clean["out"][:, others])
+    for item in ("K", "V"):
+        assert np.array_equal(dirty[item][others].view(np.uint16), clean[item][others].view(np.uint16))
+    assert np.array_equal(dirty["a"][others], clean["a"][others])
+    assert np.array_equal(dirty["pos"][others], clean["pos"][others])
+    # the unit concerned is still compressed to the budget, newest token retained
+    assert dirty["pos"].shape[1] == cfg.budget and (dirty["pos"][1, -1] == P - 1)
+
+
 def test_argument_checks():
     code = synth.DTYPE_CODE
     x = torch.zeros(64, 2, 128, dtype=torch.float16, device="cuda")
