@@ -47,12 +47,15 @@ def out_to_f64(t: torch.Tensor, dtype: str) -> np.ndarray:
     return t.to(torch.float64).cpu().numpy()
 
 
-def gpu_stream(cfg, layer=0, units_sel=None, steps=None, progress=None, **create_kw):
-    """Stream cfg through a libwkv handle.  Returns dict(out [T,U',d] f64 for the selected
+def gpu_stream(cfg, layer=0, units_sel=None, steps=None, progress=None, arrays=None, **create_kw):
+    """Stream cfg (or `arrays`: fp32 [steps, units, d] triples made by hand, rounded to storage
+    here) through a libwkv handle.  Returns dict(out [T,U',d] f64 for the selected
     units, evict_pos / evict_slot [T, units] i32, cache (open handle), inputs of the
     selected units as exact fp32)."""
     steps = cfg.steps if steps is None else steps
     st = synth.Stream(cfg, layer)
+    if arrays is not None:
+        stored = [synth.to_storage(np.ascontiguousarray(x, dtype=np.float32), cfg.dtype) for x in arrays]
     # one workgroup per unit unless a test asks otherwise (split=0 lets the library choose, as
     # the benchmark does; split>1 takes the sliced kernel)
     create_kw.setdefault("split", 1)
@@ -63,7 +66,7 @@ def gpu_stream(cfg, layer=0, units_sel=None, steps=None, progress=None, **create
     t = 0
     while t < steps:
         c = t // synth.CHUNK
-        q, k, v = st.chunk(c)
+        q, k, v = st.chunk(c) if arrays is None else (x[t:t + synth.CHUNK] for x in stored)
         n = min(q.shape[0], steps - t)
         q, k, v = q[:n], k[:n], v[:n]
         tq, tk, tv = (to_device(x, cfg.dtype) for x in (q, k, v))
@@ -205,9 +208,10 @@ def compare(cfg, g, check_state=True, log=print, **orc_kw):
     assert np.array_equal(gp, ref["evict_pos"]), "evicted token indices differ"
     assert np.array_equal(gs, ref["evict_slot"]), "evicted slot ranks differ"
     worst = check_outputs(g["out"], ref["out"], cfg.dtype)
+    with np.errstate(divide="ignore", invalid="ignore"):       # a victim's score may be exactly 0
+        rel_gap = (ref["runner_up"] - ref["evict_score"]) / ref["evict_score"]
     stats = dict(near_ties=near_ties, out_err=worst, out_exact=exact_fraction(g["out"], ref["out"], cfg.dtype),
-                 min_gap=float(np.nanmin((ref["runner_up"] - ref["evict_score"]) / ref["evict_score"]))
-                 if np.isfinite(ref["evict_score"]).any() else float("nan"))
+                 min_gap=float(np.nanmin(rel_gap)) if np.isfinite(ref["evict_score"]).any() else float("nan"))
     if check_state:
         T = g["out"].shape[0]
         stats["v_bit_exact_units"] = check_cache_state(g["cache"], ref["orc"], sel, cfg, T)

@@ -359,6 +359,36 @@ def test_two_handles_on_two_streams_do_not_interfere():
     runs[1]["cache"].close()
 
 
+def test_merges_with_a_zero_denominator():
+    """Tokens whose attention weight underflows to exactly 0 at every step have score sum 0; when
+    such a token is evicted into another one, both averages are 0 and the convex weights are
+    undefined: the two values are averaged and the case is counted in the status.  Keys of the
+    dead tokens point away from every query (logit gap of 10^4 >> 745), in runs of one to three."""
+    units, d, m, R, T = 3, 64, 24, 4, 90
+    cfg = synth.StreamConfig("zero-den", 7800, 1, units, d, "fp16", T, m, R)
+    g = np.random.default_rng(7800)
+    q = (0.5 * g.standard_normal((T, units, d))).astype(np.float32)
+    k = (0.5 * g.standard_normal((T, units, d))).astype(np.float32)
+    v = g.standard_normal((T, units, d)).astype(np.float32)
+    q[:, :, 0] = 200.0
+    dead = np.zeros((T, units), bool)
+    for u in range(units):
+        t = 2 + u
+        while t < T - 3:
+            run = int(g.integers(1, 4))
+            dead[t:t + run, u] = True
+            t += run + int(g.integers(1, 4))
+    k[:, :, 0] = np.where(dead, -200.0, 200.0)
+    res = parity.gpu_stream(cfg, arrays=(q, k, v))
+    try:
+        stats = parity.compare(cfg, res)
+        status = res["cache"].state(wkv.WKV_STATUS)
+    finally:
+        res["cache"].close()
+    print(f"\n  zero-den: {stats} status {list(status)}", flush=True)
+    assert status[0] > 0, "no merge with a zero denominator happened: the test shape is off"
+
+
 def test_a_nan_in_one_unit_is_flagged_and_stays_in_that_unit():
     """A NaN in one unit's query at one step: the status counter of non-finite scores goes up,
     that unit's output of the step is NaN, and every other unit -- outputs, evictions, cache --
