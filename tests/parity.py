@@ -172,7 +172,8 @@ def compare_prefill(cfg, g, decode_steps=0, **orc_kw):
         stats["out_exact"] = exact_fraction(g["out"], ref["out"], cfg.dtype)
     stats["v_bit_exact_units"] = check_cache_state(g["cache"], orc, sel, cfg, P)
     if ref["evict_score"].size:
-        gaps = np.diff(ref["evict_score"], axis=0) / ref["evict_score"][1:]
+        with np.errstate(divide="ignore", invalid="ignore"):   # scores may be exactly 0
+            gaps = np.diff(ref["evict_score"], axis=0) / ref["evict_score"][1:]
         stats["min_gap"] = float(gaps.min()) if gaps.size else float("nan")
     if decode_steps:
         tq, tk, tv, out = g["dev"]

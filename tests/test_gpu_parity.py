@@ -359,7 +359,8 @@ def test_two_handles_on_two_streams_do_not_interfere():
     runs[1]["cache"].close()
 
 
-def test_merges_with_a_zero_denominator():
+@pytest.mark.parametrize("split", [1, 4])
+def test_merges_with_a_zero_denominator(split):
     """Tokens whose attention weight underflows to exactly 0 at every step have score sum 0; when
     such a token is evicted into another one, both averages are 0 and the convex weights are
     undefined: the two values are averaged and the case is counted in the status.  Keys of the
@@ -379,7 +380,7 @@ def test_merges_with_a_zero_denominator():
             dead[t:t + run, u] = True
             t += run + int(g.integers(1, 4))
     k[:, :, 0] = np.where(dead, -200.0, 200.0)
-    res = parity.gpu_stream(cfg, arrays=(q, k, v))
+    res = parity.gpu_stream(cfg, arrays=(q, k, v), split=split)
     try:
         stats = parity.compare(cfg, res)
         status = res["cache"].state(wkv.WKV_STATUS)

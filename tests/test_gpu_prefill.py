@@ -141,6 +141,34 @@ def test_outputs_may_be_skipped():
         g["cache"].close()
 
 
+def test_prompt_merges_with_a_zero_denominator():
+    """Prompt tokens whose keys point away from every query get a score of exactly 0; runs of them
+    are merged with undefined convex weights: averaged, and counted in the status."""
+    units, d, m, R, P = 3, 64, 24, 4, 90
+    cfg = synth.StreamConfig("pre-zero-den", 8650, 1, units, d, "fp16", P, m, R)
+    g = np.random.default_rng(8650)
+    q = (0.5 * g.standard_normal((P, units, d))).astype(np.float32)
+    k = (0.5 * g.standard_normal((P, units, d))).astype(np.float32)
+    v = g.standard_normal((P, units, d)).astype(np.float32)
+    q[:, :, 0] = 200.0
+    dead = np.zeros((P, units), bool)
+    for u in range(units):
+        t = 2 + u
+        while t < P - 3:
+            run = int(g.integers(1, 4))
+            dead[t:t + run, u] = True
+            t += run + int(g.integers(1, 4))
+    k[:, :, 0] = np.where(dead, -200.0, 200.0)
+    res = parity.gpu_prefill(cfg, P, arrays=(q, k, v))
+    try:
+        stats = parity.compare_prefill(cfg, res)
+        status = res["cache"].state(wkv.WKV_STATUS)
+    finally:
+        res["cache"].close()
+    print(f"\n  pre-zero-den: {stats} status {list(status)}", flush=True)
+    assert status[0] > 0, "no merge with a zero denominator happened: the test shape is off"
+
+
 def test_a_nan_in_one_unit_of_the_prompt_is_flagged_and_stays_in_that_unit():
     """A NaN in one unit's query of one prompt token: non-finite scores are counted in the status,
     that row's output is NaN, and the other units' outputs and compressed caches are bit for bit
