@@ -55,11 +55,11 @@ namespace {
 //
 // Shape of the kernel (one workgroup per unit):
 //   1. small loads (query, score sums, token indices, links, incoming row), then the K
-//      rows of the first chunk, are requested before anything is waited for.  Every wave
+//      rows of the first round, are requested before anything is waited for.  Every wave
 //      issues the same loads in straight-line code: s_waitcnt counts are derived per
 //      control-flow path by the compiler, and a conditional request would make every later
 //      wait conservative;
-//   2. K phase: logits in fp64, to LDS.  A wave requests its first chunk of V rows as soon
+//   2. K phase: logits in fp64, to LDS.  A wave requests its first round of V rows as soon
 //      as it has used its last K row, so the memory system is never idle but mostly serves
 //      K before V;
 //   3. barrier 1 (LDS traffic only; the V requests stay in flight).  Then wave 0 does the
@@ -71,12 +71,12 @@ namespace {
 //      every thread writes back the score sum and link of the entry it owns; the last waves
 //      write o_t; barrier 3; the log entry.
 //
-// SEP: the incoming token is attended outside the chunked streaming (by the wave whose group
-// would have held it).  Chosen by the host when the budget is a multiple of the chunk, where
-// entry m would otherwise cost every wave one more, almost empty, chunk of K and of V.
+// SEP: the incoming token is attended outside the rounds (by the wave whose block would have
+// held it).  Chosen by the host when the budget is a multiple of the block, where entry m would
+// otherwise cost that wave one more round of K and of V for a single row.
 //
 // DED: wave 0 streams K like every other wave but takes no V rows: the V phase is spread over the
-// other waves (NG - 4 groups), and wave 0 has only the bookkeeping between the two barriers.
+// other waves, and wave 0 has only the bookkeeping between the two barriers.
 // Without it wave 0 does the bookkeeping (~2 us for 411 entries) and then its share of V, and
 // the other waves wait for it at the second barrier.  Chosen by the host (dedicated_wave below).
 template <class TT, int D, int U, int MAXT, bool SEP, bool DED, bool STREAM>
@@ -93,25 +93,44 @@ void wkv_step_kernel(WkvCache c, const void* __restrict__ q_, const void* __rest
 
     const int tid = threadIdx.x, NT = blockDim.x;
     const int NG = NT >> 4, gid = tid >> 4, sub = tid & 15;
-    const int NW = NT >> 6, wid = tid >> 6, lane = tid & 63;
+    const int NW = NT >> 6, wid = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;   // wid: scalar, so that what depends on it branches without a lane mask
     const int u = blockIdx.x;
     const int m = c.m;
     const int Lc = (t < m) ? t : m;                        // cached entries
     const int L = Lc + 1;                                  // entries attended
     const bool compress = t >= m;                          // the cache would exceed m
-    const int CH = NG * U;                                 // rows per chunk of the workgroup
-    const int Ls = SEP ? Lc : L;                           // entries streamed in chunks
-    const int nchunks = (Ls > CH) ? (Ls + CH - 1) / CH : 1;
-    const int g_in = Lc & (NG - 1);                        // SEP: the group that owns the incoming entry
-    const bool own_in = SEP && wid == (g_in >> 2);         //      and its wave
-    // V phase: which groups stream V rows
-    const int NGv = DED ? NG - 4 : NG;                     // groups that take V rows
-    const int vgid = DED ? gid - 4 : gid;                  // (negative in wave 0 with DED: unused)
+    // Rows are streamed in rounds of RB = NG * U rows: every 16-lane group takes U of them.  In a
+    // round that lies wholly inside the cache the rows are dealt group by group (row = start + gid
+    // + uu * NG), so that the requests the workgroup issues together cover consecutive rows.  The
+    // last, partial round is dealt wave by wave instead, in blocks of BR = 4 U consecutive rows,
+    // from wave 0 upwards: a wave whose block lies beyond the end skips the round, so a
+    // cache that ends in the middle of a round costs no request for what is not there (dealt group
+    // by group, the missing rows would be every wave's last requests, and leaving those out would
+    // take requests under a condition, which makes every later wait conservative).
+    constexpr int BR = 4 * U;
+    static_assert((BR & (BR - 1)) == 0, "block size must be a power of two");
+    const int g4 = gid & 3;                                // group within the wave
+    const int Ls = SEP ? Lc : L;                           // entries streamed in rounds
+    const int RB = NG * U, RBs = __builtin_ctz(RB);       // (a power of two)
+    const int nfull = Ls >> RBs;                           // full rounds
+    const int tail_blocks = (Ls - nfull * RB + BR - 1) / BR;
+    const bool in_tail = wid < tail_blocks;       // this wave has a block of the partial round
+    const int nrounds = nfull + (in_tail ? 1 : 0);         // rounds of this wave
+    // the wave that attends the incoming entry when it is kept out of the rounds (SEP; then Lc is a
+    // multiple of BR): the one that would get the block it opens
+    const int w_in = (Lc & (RB - 1)) / BR;
+    const bool own_in = SEP && wid == w_in;
+    // V phase: which waves stream V rows (all, or all but wave 0), dealt the same way among them
+    const int NWv = DED ? NW - 1 : NW, NGv = 4 * NWv;
+    const int vwid = DED ? wid - 1 : wid, vgid = DED ? gid - 4 : gid;    // (negative in wave 0 with DED: unused)
     const bool has_v = !DED || wid != 0;
-    const int CHv = NGv * U;
-    const int nchv = (Ls > CHv) ? (Ls + CHv - 1) / CHv : 1;
-    const int gv_in = DED ? ((g_in >= 4) ? g_in - 4 : 0) : g_in;   // SEP: the V group that adds the incoming value
-    const bool own_in_v = SEP && has_v && (vgid >> 2) == (gv_in >> 2);
+    const int RBv = NGv * U;
+    const int nfull_v = Ls / RBv;
+    const int tail_blocks_v = (Ls - nfull_v * RBv + BR - 1) / BR;
+    const bool in_tail_v = has_v && vwid < tail_blocks_v;
+    const int nrounds_v = nfull_v + (in_tail_v ? 1 : 0);
+    const int wv_in = (Lc % RBv) / BR;
+    const bool own_in_v = SEP && has_v && vwid == wv_in;   // SEP: the wave that adds the incoming value
 
     // ---- LDS carve-up
     extern __shared__ double lds[];
@@ -162,7 +181,7 @@ void wkv_step_kernel(WkvCache c, const void* __restrict__ q_, const void* __rest
     [[maybe_unused]] uint32_t kin[NW32];                    // SEP: the incoming key in row layout
     if constexpr (SEP) load_words<NW32>(ku + sub * LANEB, kin);
 
-    // ---- row requests.  Chunk ch of a matrix: entries gid + ch*CH + uu*NG, uu < U.
+    // ---- row requests.  Round r of a matrix: entries row_base + uu * row_stride, uu < U.
     uint32_t kw[U][NW32], vw[U][NW32];
     auto request_rows = [&](uint32_t (&dst)[U][NW32], const char* cached, const char* incoming, int base, int stride) {
         const int dup = (base < Ls) ? base : 0;            // where out-of-range groups point (harmless duplicate)
@@ -179,12 +198,16 @@ void wkv_step_kernel(WkvCache c, const void* __restrict__ q_, const void* __rest
 #pragma unroll
         for (int uu = 0; uu < U; ++uu) load_words<NW32, STREAM>(rp[uu], dst[uu]);
     };
-    auto request = [&](uint32_t (&dst)[U][NW32], const char* cached, const char* incoming, int ch) {
-        request_rows(dst, cached, incoming, ch * CH + gid, NG);
+    auto k_base = [&](int r) { return r * RB + (r < nfull ? gid : wid * BR + g4); };
+    auto k_stride = [&](int r) { return r < nfull ? NG : 4; };
+    auto v_base = [&](int r) { return r * RBv + (r < nfull_v ? vgid : vwid * BR + g4); };
+    auto v_stride = [&](int r) { return r < nfull_v ? NGv : 4; };
+    auto request = [&](uint32_t (&dst)[U][NW32], const char* cached, const char* incoming, int r) {
+        request_rows(dst, cached, incoming, k_base(r), k_stride(r));
     };
-    auto request_v = [&](int ch) { request_rows(vw, Vc, vu, ch * CHv + vgid, NGv); };
+    auto request_v = [&](int r) { request_rows(vw, Vc, vu, v_base(r), v_stride(r)); };
 
-    request(kw, Kc, ku, 0);
+    request(kw, Kc, ku, 0);                                // a wave without a round gets harmless duplicates
 
     double qd[EPL];                                        // the query, pre-scaled by 1/sqrt(d), in fp64
     {
@@ -197,11 +220,11 @@ void wkv_step_kernel(WkvCache c, const void* __restrict__ q_, const void* __rest
 
     // ---- K phase: logits q.K / sqrt(d) in fp64, to LDS
     double mx = -INFINITY;
-    auto logits = [&](int ch) {
-        const int base = ch * CH + gid;
+    auto logits = [&](int r) {
+        const int base = k_base(r), stride = k_stride(r);
 #pragma unroll
         for (int uu = 0; uu < U; ++uu) {
-            const int i = base + uu * NG;
+            const int i = base + uu * stride;
             float kx[EPL];
             decode<TT, EPL, NW32>(kw[uu], kx);
             double dot = 0.0;
@@ -222,12 +245,15 @@ void wkv_step_kernel(WkvCache c, const void* __restrict__ q_, const void* __rest
 #pragma unroll
             for (int e = 0; e < EPL; ++e) dot = fma((double)kx[e], qd[e], dot);
             dot = row_allsum(dot);
-            if (gid == g_in && sub == 0) sl[Lc] = dot;
+            if (lane == 0) sl[Lc] = dot;
             mx = fmax(mx, dot);
         }
     }
-    for (int ch = 0; ch + 1 < nchunks; ++ch) { logits(ch); request(kw, Kc, ku, ch + 1); }
-    logits(nchunks - 1);
+    {
+        int r = 0;
+        for (; r + 1 < nrounds; ++r) { logits(r); request(kw, Kc, ku, r + 1); }
+        if (r < nrounds) logits(r);
+    }
     [[maybe_unused]] uint32_t vin[NW32];                    // SEP: the incoming value in row layout
     if constexpr (SEP) load_words<NW32>(vu + sub * LANEB, vin);
     // stage what the bookkeeping needs (these loads are older than the K rows: they have
@@ -249,10 +275,13 @@ void wkv_step_kernel(WkvCache c, const void* __restrict__ q_, const void* __rest
     // fp64 exponentials of the softmax are spread over all waves, ahead of the barrier
     {
         double psum = 0.0;
-        const int per_group = (L + NG - 1) / NG;
-        for (int idx = lane; idx < 4 * per_group; idx += 64) {
-            const int i = (4 * wid + (idx & 3)) + NG * (idx >> 2);
-            if (i < L) { const double e = exp(sl[i] - mx); el[i] = e; psum += e; }
+        for (int idx = lane; idx < nrounds * BR; idx += 64) {
+            const int r = idx / BR, j = idx & (BR - 1);
+            const int i = r * RB + (r < nfull ? (j >> 2) * NG + 4 * wid + (j & 3) : wid * BR + j);
+            if (i < Ls) { const double e = exp(sl[i] - mx); el[i] = e; psum += e; }
+        }
+        if constexpr (SEP) {
+            if (own_in && lane == 0) { const double e = exp(sl[Lc] - mx); el[Lc] = e; psum += e; }
         }
         psum = wave_sum(psum);
         if (lane == 0) { wmax[wid] = mx; wsum[wid] = psum; }
@@ -291,7 +320,8 @@ void wkv_step_kernel(WkvCache c, const void* __restrict__ q_, const void* __rest
                     const int i = b0 + 64 * k + lane;
                     const int ic = (i < L) ? i : L - 1;              // past the end: a duplicate, never stored or ranked
                     e[k] = el[ic]; a[k] = al[ic]; pi[k] = pl[ic];
-                    f[k] = fw[(ic & (NG - 1)) >> 2];
+                    const int ir = ic & (RB - 1);                    // the wave that produced the entry
+                    f[k] = fw[(ic == Lc && SEP) ? w_in : (ic - ir < nfull * RB) ? (ir & (NG - 1)) >> 2 : ir / BR];
                 }
                 double p[BK], ai[BK];
 #pragma unroll
@@ -366,11 +396,11 @@ void wkv_step_kernel(WkvCache c, const void* __restrict__ q_, const void* __rest
     S acc[EPL];
 #pragma unroll
     for (int e = 0; e < EPL; ++e) acc[e] = (S)0;
-    auto weighted_sum = [&](int ch) {
-        const int base = ch * CHv + vgid;
+    auto weighted_sum = [&](int r) {
+        const int base = v_base(r), stride = v_stride(r);
 #pragma unroll
         for (int uu = 0; uu < U; ++uu) {
-            const int i = base + uu * NGv;
+            const int i = base + uu * stride;
             const S p = (i < Ls) ? soft_exp((S)(sl[(i < Ls) ? i : 0] - Mx)) : (S)0;
             // The row is touched here and not before: left alone, the compiler converts the first V
             // rows right behind their request, ahead of the first barrier, and every wave then
@@ -385,10 +415,10 @@ void wkv_step_kernel(WkvCache c, const void* __restrict__ q_, const void* __rest
         }
     };
     if (has_v) {
-        weighted_sum(0);                                   // the chunk requested during the K phase
+        if (nrounds_v > 0) weighted_sum(0);                // the round requested during the K phase
         if constexpr (SEP) {
             if (own_in_v) {                                // the incoming token, counted by one group only
-                const S p = (vgid == gv_in) ? soft_exp((S)(sl[Lc] - Mx)) : (S)0;
+                const S p = (g4 == 0) ? soft_exp((S)(sl[Lc] - Mx)) : (S)0;
                 float vx[EPL];
                 decode<TT, EPL, NW32>(vin, vx);
                 l_run += p;
@@ -396,7 +426,7 @@ void wkv_step_kernel(WkvCache c, const void* __restrict__ q_, const void* __rest
                 for (int e = 0; e < EPL; ++e) acc[e] += p * (S)vx[e];
             }
         }
-        for (int ch = 1; ch < nchv; ++ch) { request_v(ch); weighted_sum(ch); }
+        for (int r = 1; r < nrounds_v; ++r) { request_v(r); weighted_sum(r); }
     }
     if (has_v) {                                           // a wave without V rows has nothing to add
         S l_w = l_run;
@@ -501,26 +531,26 @@ void wkv_step_kernel(WkvCache c, const void* __restrict__ q_, const void* __rest
     WKV_MARK(7);
 }
 
-// Chunk sizes a workgroup may stream with.  Deep chunks (U rows per group) keep more bytes in
-// flight per wave; but the last chunk of a matrix is padded with repeated rows, and when m + 1
-// sits just above a multiple of the chunk that padding is up to half of all row requests.
-// Workgroups of up to 512 threads therefore exist with U and with U / 2 rows per group, and the
-// host takes the shallower one when it saves at least a tenth of the row requests
-// (MI355X, 1024 units x 520 slots bf16, 512 threads: 50.4 -> 47.4 us per step).
-template <class TT, int D, int MAXT> constexpr bool has_half_chunk() { return MAXT <= 512 && unroll<TT, D, MAXT>() >= 8; }
+// The incoming token is attended outside the rounds (SEP at the kernel) when it alone would open
+// another block of rows, i.e. cost one wave another round of K and of V for a single row.
+inline bool separate_incoming(int m, int rows_per_group) { return m % (4 * rows_per_group) == 0; }
 
-// row requests per matrix and group-row when streaming m (+1) entries in chunks of ch rows
-inline int row_slots(int m, int ch, bool* sep)
+// Depth of a round.  Deep rounds (U rows per group) keep more bytes in flight per wave; shallow
+// ones leave more, smaller steps for the workgroups of a compute unit to interleave.  Workgroups
+// of up to 512 threads exist with U and with U / 2 rows per group; the shallower one is taken
+// when m + 1 sits just above a multiple of the deep round -- measured, MI355X, 1024 units x 520
+// slots bf16, 256 threads: 51.8 us per step with U = 8 (and 49.9 with 512 threads), 47.9 with U = 4.
+template <class TT, int D, int MAXT> constexpr bool has_half_chunk() { return MAXT <= 512 && unroll<TT, D, MAXT>() >= 8; }
+inline int round_slots(int m, int round) { const int ls = (m % round == 0) ? m : m + 1; return (ls + round - 1) / round * round; }
+inline bool shallow_rounds(int m, int ng, int rows_per_group)
 {
-    *sep = (m % ch) == 0;          // the incoming token alone would open another chunk: attend it outside
-    const int ls = *sep ? m : m + 1;
-    return (ls + ch - 1) / ch * ch;
+    return round_slots(m, ng * (rows_per_group / 2)) * 10 <= round_slots(m, ng * rows_per_group) * 9;
 }
 
 // Wave 0 is kept free of V rows (DED at the kernel) in the 1024-thread workgroups always; in
 // the smaller ones when the launch is not large enough for many workgroups per compute unit to
-// overlap each other's serial stretches, and the V rows still fit the same number of chunks
-// with four groups fewer.  Measured (512 threads, d = 128, 16-bit, us per step with / without):
+// overlap each other's serial stretches, and the V rows still fit the same number of rounds
+// with one wave fewer.  Measured (512 threads, d = 128, 16-bit, us per step with / without):
 // 384 units x 410 slots 21.1 / 22.3, 512 x 410 23.8 / 24.8, 1024 x 520 55.0 / 55.2, 2048 x 512
 // 102.1 / 102.4; one more chunk of V: 512 x 1024 54.2 / 53.9, 4096 x 256 150.6 / 104.0.
 inline bool dedicated_wave(const WkvCache& c, int threads, size_t row_bytes, int rows_per_group, bool sep)
@@ -600,16 +630,11 @@ hipError_t launch(const WkvCache& c, int threads, size_t lds, bool stream_loads,
                   const void* v, void* out, int t, hipStream_t stream)
 {
     constexpr int U = unroll<TT, D, MAXT>();
-    const int ng = threads / ROW_LANES;
-    bool sep;
-    const int slots = row_slots(c.m, ng * U, &sep);
     if constexpr (has_half_chunk<TT, D, MAXT>()) {
-        bool sep_half;
-        const int slots_half = row_slots(c.m, ng * (U / 2), &sep_half);
-        if (slots_half * 10 <= slots * 9)
-            return launch_u<TT, D, U / 2, MAXT>(c, threads, lds, sep_half, stream_loads, q, k, v, out, t, stream);
+        if (shallow_rounds(c.m, threads / ROW_LANES, U))
+            return launch_u<TT, D, U / 2, MAXT>(c, threads, lds, separate_incoming(c.m, U / 2), stream_loads, q, k, v, out, t, stream);
     }
-    return launch_u<TT, D, U, MAXT>(c, threads, lds, sep, stream_loads, q, k, v, out, t, stream);
+    return launch_u<TT, D, U, MAXT>(c, threads, lds, separate_incoming(c.m, U), stream_loads, q, k, v, out, t, stream);
 }
 
 }  // namespace
@@ -628,13 +653,10 @@ template <class TT, int D, int MAXT> int padded_rows(int m, int threads)
 {
     constexpr int U = unroll<TT, D, MAXT>();
     const int ng = threads / ROW_LANES;
-    bool sep;
-    int slots = row_slots(m, ng * U, &sep);
     if constexpr (has_half_chunk<TT, D, MAXT>()) {
-        const int slots_half = row_slots(m, ng * (U / 2), &sep);
-        if (slots_half * 10 <= slots * 9) slots = slots_half;
+        if (shallow_rounds(m, ng, U)) return round_slots(m, ng * (U / 2));
     }
-    return slots;
+    return round_slots(m, ng * U);
 }
 }  // namespace
 
