@@ -44,7 +44,7 @@ void wkv_split_kernel(WkvCache c, WkvSplit sp, const void* __restrict__ q_, cons
 
     const int tid = threadIdx.x, NT = blockDim.x;
     const int NG = NT >> 4, gid = tid >> 4, sub = tid & 15;
-    const int NW = NT >> 6, wid = tid >> 6, lane = tid & 63;
+    const int NW = NT >> 6, wid = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
     const int NS = sp.S;
     const int u = blockIdx.x / NS, s = blockIdx.x - u * NS;
     const int m = c.m;
@@ -54,8 +54,15 @@ void wkv_split_kernel(WkvCache c, WkvSplit sp, const void* __restrict__ q_, cons
     const int per = (L + NS - 1) / NS;                     // entries per slice
     const int lo = (s * per < L) ? s * per : L;            // this slice: entries lo .. hi-1 (may be empty)
     const int hi = (lo + per < L) ? lo + per : L;
-    const int CH = NG * U;
-    const int nchunks = (hi - lo > CH) ? (hi - lo + CH - 1) / CH : 1;
+    // Rounds of RB = NG * U rows; full rounds are dealt group by group, the last, partial one wave
+    // by wave in blocks of BR = 4 U consecutive rows from wave 0 upwards, and a wave whose block
+    // lies beyond the end of the slice skips it (as in wkv_step.hip, where the reasons are given).
+    constexpr int BR = 4 * U;
+    const int g4 = gid & 3;
+    const int RB = NG * U;
+    const int nfull = (hi - lo) >> __builtin_ctz(RB);
+    const int tail_blocks = (hi - lo - nfull * RB + BR - 1) / BR;
+    const int nrounds = nfull + (wid < tail_blocks ? 1 : 0);   // rounds of this wave
 
     // ---- LDS carve-up
     extern __shared__ double lds[];
@@ -89,15 +96,17 @@ void wkv_split_kernel(WkvCache c, WkvSplit sp, const void* __restrict__ q_, cons
     // =========================================================== phase A: the slice
     uint32_t qw[NW32];
     load_words<NW32>(qu + sub * LANEB, qw);
-    // Chunk ch of the slice: entries lo + gid + ch*CH + uu*NG, uu < U.  Entry Lc is the incoming
-    // token, read from the caller's buffers.  Out-of-range groups re-read a valid row.
+    // Round r of the slice: entries row_base(r) + uu * row_stride(r), uu < U.  Entry Lc is the incoming
+    // token, read from the caller's buffers.  Rows past the end of the slice re-read a valid row.
+    auto row_base = [&](int r) { return lo + r * RB + (r < nfull ? gid : wid * BR + g4); };
+    auto row_stride = [&](int r) { return r < nfull ? NG : 4; };
     uint32_t kw[U][NW32], vw[U][NW32];
-    auto request = [&](uint32_t (&dst)[U][NW32], const char* cached, const char* incoming, int ch) {
-        const int base = lo + ch * CH + gid;
+    auto request = [&](uint32_t (&dst)[U][NW32], const char* cached, const char* incoming, int r) {
+        const int base = row_base(r), stride = row_stride(r);
         const int dup = (base < hi) ? base : 0;            // entry 0 always has an address (slot 0, or the incoming row)
 #pragma unroll
         for (int uu = 0; uu < U; ++uu) {
-            int i = base + uu * NG;
+            int i = base + uu * stride;
             if (i >= hi) i = dup;
             const char* rp = (i == Lc) ? incoming : cached + (size_t)i * ROWB;
             load_words<NW32, STREAM>(rp + sub * LANEB, dst[uu]);
@@ -115,11 +124,11 @@ void wkv_split_kernel(WkvCache c, WkvSplit sp, const void* __restrict__ q_, cons
     }
 
     double mx = -INFINITY;
-    auto logits = [&](int ch) {
-        const int base = lo + ch * CH + gid;
+    auto logits = [&](int r) {
+        const int base = row_base(r), stride = row_stride(r);
 #pragma unroll
         for (int uu = 0; uu < U; ++uu) {
-            const int i = base + uu * NG;
+            const int i = base + uu * stride;
             float kx[EPL];
             decode<TT, EPL, NW32>(kw[uu], kx);
             double dot = 0.0;
@@ -132,8 +141,11 @@ void wkv_split_kernel(WkvCache c, WkvSplit sp, const void* __restrict__ q_, cons
             }
         }
     };
-    for (int ch = 0; ch + 1 < nchunks; ++ch) { logits(ch); request(kw, Kc, ku, ch + 1); }
-    logits(nchunks - 1);
+    {
+        int r = 0;
+        for (; r + 1 < nrounds; ++r) { logits(r); request(kw, Kc, ku, r + 1); }
+        if (r < nrounds) logits(r);
+    }
     request(vw, Vc, vu, 0);
 
     mx = fmax(fmax(readlane_f64(mx, 0), readlane_f64(mx, 16)), fmax(readlane_f64(mx, 32), readlane_f64(mx, 48)));
@@ -163,11 +175,11 @@ void wkv_split_kernel(WkvCache c, WkvSplit sp, const void* __restrict__ q_, cons
     S acc[EPL];
 #pragma unroll
     for (int e = 0; e < EPL; ++e) acc[e] = (S)0;
-    auto weighted_sum = [&](int ch) {
-        const int base = lo + ch * CH + gid;
+    auto weighted_sum = [&](int r) {
+        const int base = row_base(r), stride = row_stride(r);
 #pragma unroll
         for (int uu = 0; uu < U; ++uu) {
-            const int i = base + uu * NG;
+            const int i = base + uu * stride;
             const S p = (i < hi) ? soft_exp((S)(sl[(i < hi) ? i - lo : 0] - Ms)) : (S)0;
             // touched here and not before: left alone, the compiler converts the first V rows right
             // behind their request, i.e. waits for them ahead of the barrier (see wkv_step.hip)
@@ -180,8 +192,8 @@ void wkv_split_kernel(WkvCache c, WkvSplit sp, const void* __restrict__ q_, cons
             for (int e = 0; e < EPL; ++e) acc[e] += p * (S)vx[e];
         }
     };
-    weighted_sum(0);
-    for (int ch = 1; ch < nchunks; ++ch) { request(vw, Vc, vu, ch); weighted_sum(ch); }
+    if (nrounds > 0) weighted_sum(0);
+    for (int r = 1; r < nrounds; ++r) { request(vw, Vc, vu, r); weighted_sum(r); }
     {
         l_run = rows_sum(l_run);                           // over the wave's four groups
 #pragma unroll
