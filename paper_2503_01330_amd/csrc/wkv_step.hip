@@ -550,19 +550,26 @@ inline bool shallow_rounds(int m, int ng, int rows_per_group)
     return round_slots(m, ng * (rows_per_group / 2)) * 10 <= round_slots(m, ng * rows_per_group) * 9;
 }
 
-// Wave 0 is kept free of V rows (DED at the kernel) in the 1024-thread workgroups always; in
-// the smaller ones when the launch is not large enough for many workgroups per compute unit to
-// overlap each other's serial stretches, and the V rows still fit the same number of rounds
-// with one wave fewer.  Measured (512 threads, d = 128, 16-bit, us per step with / without):
-// 384 units x 410 slots 21.1 / 22.3, 512 x 410 23.8 / 24.8, 1024 x 520 55.0 / 55.2, 2048 x 512
-// 102.1 / 102.4; one more chunk of V: 512 x 1024 54.2 / 53.9, 4096 x 256 150.6 / 104.0.
+// Wave 0 is kept free of V rows (DED at the kernel) in the 1024-thread workgroups always.  In
+// those of 512 threads when a matrix takes three rounds or more (one wave fewer among eight then
+// adds little to each of the others, and wave 0's bookkeeping stops being the longest job of the
+// workgroup); with fewer rounds, and in workgroups of 256 threads, only when the launch is not
+// large enough for many workgroups per compute unit to overlap each other's serial stretches
+// and the V rows still fit the same number of rounds with one wave fewer.  Measured (512 threads,
+// d = 128, 16-bit, us per step with / without): 384 units x 410 slots 19.7 / 20.2, 512 x 410
+// 22.4 / 23.0, 4096 x 300 (three rounds of four rows) 110.7 / 118.4, 2048 x 350 65.8 / 68.9,
+// 512 x 1024 48.7 / 52.1, 1024 x 640 57.0 / 59.4, 1024 x 1024 92.2 / 94.5, 2048 x 1024 184.0 /
+// 187.9; two rounds: 2048 x 512 91.2 / 91.4, 8192 x 512 360.9 / 355.6, 2048 x 410 76.8 / 76.3;
+// one round: 4096 x 256 99.1 / 97.8; 256 threads: 768 x 410 29.9 / 29.3.
 inline bool dedicated_wave(const WkvCache& c, int threads, size_t row_bytes, int rows_per_group, bool sep)
 {
     if (threads > 512) return true;
     const int ls = sep ? c.m : c.m + 1, ng = threads / ROW_LANES;
     const int chunk = ng * rows_per_group, chunk_v = (ng - 4) * rows_per_group;
-    const bool same_chunks = (ls + chunk - 1) / chunk == (ls + chunk_v - 1) / chunk_v;
-    return same_chunks && (size_t)c.units * (size_t)(c.m + 1) * row_bytes * 2 <= (size_t)400 << 20;
+    const int rounds = (ls + chunk - 1) / chunk, rounds_v = (ls + chunk_v - 1) / chunk_v;
+    const bool small = (size_t)c.units * (size_t)(c.m + 1) * row_bytes * 2 <= (size_t)400 << 20;
+    if (threads == 512 && rounds >= 3) return true;
+    return rounds == rounds_v && small;
 }
 
 template <class TT, int D, int U, int MAXT>

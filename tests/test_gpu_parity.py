@@ -224,10 +224,11 @@ def test_cfg5_batched_bf16_sampled_units():
 
 @pytest.mark.parametrize("dtype,d,batch", [("fp16", 128, 64), ("fp32", 64, 64), ("bf16", 64, 128), ("bf16", 256, 32)])
 def test_large_launches_where_no_wave_is_set_aside(dtype, d, batch):
-    """Launches of more than 400 MiB of K and V in workgroups of at most 512 threads run the
-    variant in which wave 0 streams V rows like the others and does the bookkeeping first (small
-    launches, i.e. every other test but cfg5, set a wave aside for it).  One shape per row width;
-    the budget is no multiple of the chunk, unlike cfg5's.  Sampled units go through the oracle."""
+    """Launches of more than 400 MiB of K and V in workgroups of at most 512 threads whose rows
+    take one or two rounds run the variant in which wave 0 streams V rows like the others and
+    does the bookkeeping first (small launches, and those of three rounds or more -- the 512-byte
+    rows here -- set a wave aside for it).  One shape per row width; the budget is no multiple of
+    the round, unlike cfg5's.  Sampled units go through the oracle."""
     m, heads = 410, 32
     row_bytes = d * (4 if dtype == "fp32" else 2)
     assert batch * heads * (m + 1) * row_bytes * 2 > 400 << 20
