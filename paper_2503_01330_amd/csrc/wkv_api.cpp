@@ -107,12 +107,12 @@ int validate(const wkv_options& o, int* threads, int* split)
         // units), except for 128-byte rows, where 256 threads are 20 % ahead; slices: 512
         const int row_bytes = o.head_dim * dtype_bytes(o.dtype);
         th = sp > 1 ? 512 : units >= 1024 ? (row_bytes < 256 ? 256 : 512) : units > 256 ? 512 : 1024;
-        // from 768 to about 1500 units, 256 threads where m + 1 sits clearly closer above a multiple
+        // from 768 to about 1200 units, 256 threads where m + 1 sits clearly closer above a multiple
         // of their (smaller) round than of the 512-thread one (m = 410: 448 against 512 rows):
-        // 768 x 410 31.2 -> 29.8 us, 1024 x 410 40.3 -> 38.1, 1024 x 520 49.4 -> 47.7; where the two
-        // are equally close (m = 512) 512 threads stay 0.3-2.5 % ahead, and from 2048 units on they
-        // win either way (2048 x 410: 77.2 against 79.0); below 768 units too
-        if (sp == 1 && units >= 768 && units < 1536 && row_bytes == 256 && th == 512 && fits(256) &&
+        // 768 x 410 30.5 -> 29.3 us, 1024 x 410 39.4 -> 37.5, 1024 x 520 49.3 -> 46.8; where the two
+        // are equally close (m = 512) 512 threads stay ahead, and beyond they win either way
+        // (1400 x 410: 55.3 against 58.6, 2048 x 410: 77.2 against 79.0); below 768 units too
+        if (sp == 1 && units >= 768 && units < 1200 && row_bytes == 256 && th == 512 && fits(256) &&
             wkv_step_padded_rows(o.budget, o.dtype, o.head_dim, 256) * 20 <=
             wkv_step_padded_rows(o.budget, o.dtype, o.head_dim, 512) * 19)
             th = 256;

@@ -539,14 +539,19 @@ void wkv_step_kernel(WkvCache c, const void* __restrict__ q_, const void* __rest
 inline bool separate_incoming(int m, int rows_per_group) { return m % (4 * rows_per_group) == 0; }
 
 // Depth of a round.  Deep rounds (U rows per group) keep more bytes in flight per wave; shallow
-// ones leave more, smaller steps for the workgroups of a compute unit to interleave.  Workgroups
-// of up to 512 threads exist with U and with U / 2 rows per group; the shallower one is taken
-// when m + 1 sits just above a multiple of the deep round -- measured, MI355X, 1024 units x 520
-// slots bf16, 256 threads: 51.8 us per step with U = 8 (and 49.9 with 512 threads), 47.9 with U = 4.
+// ones leave more, smaller steps for the workgroups of a compute unit to interleave, and more
+// rounds make the dedicated bookkeeping wave pay (below).  Workgroups of up to 512 threads exist
+// with U and with U / 2 rows per group.  The shallower one is taken by 512-thread workgroups in
+// launches of up to 1024 units (MI355X, d = 128, 16-bit, us per step: 384 units x 410 slots 19.7
+// -> 18.7, 512 x 410 22.3 -> 20.7, 512 x 1024 48.8 -> 44.9, 1024 x 512 48.7 -> 46.0, 1024 x 1024
+// 92.3 -> 87.8; larger launches lose: 2048 x 512 91.7 -> 92.5, 8192 x 512 356 -> 371, 4096 x 256
+// 98 -> 106), and otherwise when m + 1 sits just above a multiple of the deep round (1024 units x
+// 520 slots bf16, 256 threads: 51.8 with U = 8, 47.9 with U = 4).
 template <class TT, int D, int MAXT> constexpr bool has_half_chunk() { return MAXT <= 512 && unroll<TT, D, MAXT>() >= 8; }
 inline int round_slots(int m, int round) { const int ls = (m % round == 0) ? m : m + 1; return (ls + round - 1) / round * round; }
-inline bool shallow_rounds(int m, int ng, int rows_per_group)
+inline bool shallow_rounds(int m, int ng, int rows_per_group, int units = 1 << 30)
 {
+    if (units <= 1024 && ng == 32) return true;
     return round_slots(m, ng * (rows_per_group / 2)) * 10 <= round_slots(m, ng * rows_per_group) * 9;
 }
 
@@ -641,7 +646,7 @@ hipError_t launch(const WkvCache& c, int threads, size_t lds, bool stream_loads,
 {
     constexpr int U = unroll<TT, D, MAXT>();
     if constexpr (has_half_chunk<TT, D, MAXT>()) {
-        if (shallow_rounds(c.m, threads / ROW_LANES, U))
+        if (shallow_rounds(c.m, threads / ROW_LANES, U, c.units))
             return launch_u<TT, D, U / 2, MAXT>(c, threads, lds, separate_incoming(c.m, U / 2), stream_loads, q, k, v, out, t, stream);
     }
     return launch_u<TT, D, U, MAXT>(c, threads, lds, separate_incoming(c.m, U), stream_loads, q, k, v, out, t, stream);
