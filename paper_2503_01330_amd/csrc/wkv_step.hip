@@ -69,7 +69,8 @@ namespace {
 //   4. barrier 2: victim and neighbour are known.  Wave 0, which requested the two V rows of
 //      the merge as soon as it knew them, writes the merged row and the incoming token's rows;
 //      every thread writes back the score sum and link of the entry it owns; the last waves
-//      write o_t; barrier 3; the log entry.
+//      write o_t; barrier 3; the log entry (the 1024-thread workgroups need no third barrier:
+//      their wave 0 has ranked the victim for the log while it waited for the second).
 //
 // SEP: the incoming token is attended outside the rounds (by the wave whose block would have
 // held it).  Chosen by the host when the budget is a multiple of the block, where entry m would
@@ -85,6 +86,7 @@ void wkv_step_kernel(WkvCache c, const void* __restrict__ q_, const void* __rest
                      const void* __restrict__ v_, void* __restrict__ out_, int t)
 {
     using S = typename TT::soft_t;
+    constexpr bool RANK0 = DED && MAXT > 512;    // wave 0 also ranks the victim for the log
     constexpr int EPL  = D / ROW_LANES;          // elements of a row per lane
     constexpr int NW32 = EPL * TT::BYTES / 4;    // 32-bit words per lane per row
     constexpr int ROWB = D * TT::BYTES;          // bytes per row
@@ -390,6 +392,16 @@ void wkv_step_kernel(WkvCache c, const void* __restrict__ q_, const void* __rest
                     atomicAdd(&c.status[1], 1);
                 }
             }
+            if constexpr (RANK0) {
+                // the victim's rank in token order, for the log: this wave has nothing else to do
+                // until the second barrier, and the other waves are spared a count, a reduction, an
+                // LDS atomic and a third barrier at the very end of the kernel (cfg3 13.4 -> 13.2 us;
+                // in the 512-thread workgroups of large launches it does not pay: 1024 x 1024 88.2 -> 89.4)
+                int cnt = 0;
+                for (int i = lane; i < Lc; i += 64) cnt += (pl[i] < best.pos) ? 1 : 0;
+                cnt = wave_sum(cnt);
+                if (lane == 0) bk_i[4] = cnt;
+            }
         }
         WKV_MARK(8);
     }
@@ -503,7 +515,7 @@ void wkv_step_kernel(WkvCache c, const void* __restrict__ q_, const void* __rest
             if (k * NT < L) {                               // uniform: skip rounds no thread needs
                 const int i = tid + k * NT;
                 if (i < Lc) {
-                    cnt += (pos_reg[k] < pj) ? 1 : 0;       // the victim's rank in token order, for the log
+                    if constexpr (!RANK0) cnt += (pos_reg[k] < pj) ? 1 : 0;   // the victim's rank in token order, for the log
                     if (i != j) {
                         au[i] = al[i];
                         const int n = nxt_reg[k];
@@ -517,13 +529,15 @@ void wkv_step_kernel(WkvCache c, const void* __restrict__ q_, const void* __rest
                 }
             }
         }
-        if (compress) {
-            cnt = wave_sum(cnt);
-            if (lane == 0 && cnt) atomicAdd(&bk_i[4], cnt);
+        if constexpr (!RANK0) {
+            if (compress) {
+                cnt = wave_sum(cnt);
+                if (lane == 0 && cnt) atomicAdd(&bk_i[4], cnt);
+            }
         }
     }
     WKV_MARK(6);
-    WKV_LDS_BARRIER();   // barrier 3: the victim's rank is complete (global stores keep flying)
+    if constexpr (!RANK0) WKV_LDS_BARRIER();   // barrier 3: the victim's rank is complete (global stores keep flying)
 #undef WKV_LDS_BARRIER
 
     if (tid == 0) {
