@@ -94,6 +94,17 @@ def test_budgets_just_above_a_chunk_take_the_shallower_chunk(dtype, d, threads):
 
 
 # ---- the sliced kernel (several workgroups per unit, for caches with few units)
+@pytest.mark.parametrize("threads", [256, 512, 1024])
+def test_budgets_around_blocks_and_rounds(threads):
+    """Budgets just below, at and just above multiples of a block of rows (8, 16 or 32, by shape) and
+    of a whole round of the workgroup: the partial round is dealt to the first waves only, and the
+    incoming token is attended outside the rounds exactly when the budget is a multiple of the block."""
+    for n, m in enumerate([15, 16, 17, 31, 32, 33, 48, 64, 96, 127, 128, 129, 144, 160, 255, 256, 257, 272, 288]):
+        dtype, d = [("fp16", 128), ("bf16", 64), ("fp32", 64)][n % 3]
+        cfg = synth.StreamConfig(f"blk-{threads}-{m}", 7900 + m, 1, 3, d, dtype, m + 24, m, 1 + n % 5)
+        _run(cfg, threads=threads)
+
+
 @pytest.mark.parametrize("split", [2, 4, 8, 16])
 def test_sliced_units_small_shapes(split):
     """Every slice count against the oracle: slices that are empty while the cache fills (and for
