@@ -86,7 +86,9 @@ void wkv_step_kernel(WkvCache c, const void* __restrict__ q_, const void* __rest
                      const void* __restrict__ v_, void* __restrict__ out_, int t)
 {
     using S = typename TT::soft_t;
-    constexpr bool RANK0 = DED && MAXT > 512;    // wave 0 also ranks the victim for the log
+    // wave 0 also ranks the victim for the log: in the 1024-thread workgroups, and in smaller ones
+    // with a dedicated wave when the launch is small (uniform over the launch)
+    const bool RANK0 = DED && (MAXT > 512 || gridDim.x <= 768);
     constexpr int EPL  = D / ROW_LANES;          // elements of a row per lane
     constexpr int NW32 = EPL * TT::BYTES / 4;    // 32-bit words per lane per row
     constexpr int ROWB = D * TT::BYTES;          // bytes per row
@@ -392,11 +394,12 @@ void wkv_step_kernel(WkvCache c, const void* __restrict__ q_, const void* __rest
                     atomicAdd(&c.status[1], 1);
                 }
             }
-            if constexpr (RANK0) {
+            if (RANK0) {
                 // the victim's rank in token order, for the log: this wave has nothing else to do
                 // until the second barrier, and the other waves are spared a count, a reduction, an
-                // LDS atomic and a third barrier at the very end of the kernel (cfg3 13.4 -> 13.2 us;
-                // in the 512-thread workgroups of large launches it does not pay: 1024 x 1024 88.2 -> 89.4)
+                // LDS atomic and a third barrier at the very end of the kernel (cfg3 13.4 -> 13.2 us,
+                // 512 units x 410 slots 21.2 -> 20.9; in large launches it does not pay: 1024 x 1024
+                // 88.2 -> 89.4)
                 int cnt = 0;
                 for (int i = lane; i < Lc; i += 64) cnt += (pl[i] < best.pos) ? 1 : 0;
                 cnt = wave_sum(cnt);
@@ -515,7 +518,7 @@ void wkv_step_kernel(WkvCache c, const void* __restrict__ q_, const void* __rest
             if (k * NT < L) {                               // uniform: skip rounds no thread needs
                 const int i = tid + k * NT;
                 if (i < Lc) {
-                    if constexpr (!RANK0) cnt += (pos_reg[k] < pj) ? 1 : 0;   // the victim's rank in token order, for the log
+                    if (!RANK0) cnt += (pos_reg[k] < pj) ? 1 : 0;   // the victim's rank in token order, for the log
                     if (i != j) {
                         au[i] = al[i];
                         const int n = nxt_reg[k];
@@ -529,7 +532,7 @@ void wkv_step_kernel(WkvCache c, const void* __restrict__ q_, const void* __rest
                 }
             }
         }
-        if constexpr (!RANK0) {
+        if (!RANK0) {
             if (compress) {
                 cnt = wave_sum(cnt);
                 if (lane == 0 && cnt) atomicAdd(&bk_i[4], cnt);
@@ -537,7 +540,7 @@ void wkv_step_kernel(WkvCache c, const void* __restrict__ q_, const void* __rest
         }
     }
     WKV_MARK(6);
-    if constexpr (!RANK0) WKV_LDS_BARRIER();   // barrier 3: the victim's rank is complete (global stores keep flying)
+    if (!RANK0) WKV_LDS_BARRIER();   // barrier 3: the victim's rank is complete (global stores keep flying)
 #undef WKV_LDS_BARRIER
 
     if (tid == 0) {
