@@ -1,111 +1,141 @@
-"""TEST INFRASTRUCTURE ONLY -- pure-Python, list-based simulation of WeightedKV.
+"""TEST INFRASTRUCTURE ONLY -- a token-table simulation of WeightedKV for tiny inputs.
 
-One (sequence, head) unit, Python floats (IEEE double), Python lists with
-`append` and `del`: the shape of the paper's Algorithm 1 taken literally, slow
-and meant for tiny inputs.  It exists to pin the C oracle (wkv_oracle.c): the
-two are written separately and must agree exactly on small random streams.
+One (sequence, head) unit.  Where the C oracle (wkv_oracle.c) keeps ordered arrays and an
+explicit list of counts, this simulator keeps a table keyed by token index: every retained
+token owns a record with its key, its (possibly merged) value, the attention mass it has
+collected, the step at which it entered and the weight it got in the latest step.  Counts are
+not stored: a token that entered at step b has been attended b..t, i.e. t - b + 1 times.
+Token order is the order of the table's keys.  Python floats (IEEE double) throughout.
+
+It exists to pin the C oracle: the two are written separately, organised differently, and
+must agree on small random streams -- for WeightedKV itself (Algorithm 1, Section IV) and for
+the variants around it: dropping the value instead of merging it (the ablation of Section V-B)
+and ranking by accumulated mass or by the latest weight (the two eviction rules described in
+Section II).
 
 Readings taken where the paper is silent:
   * logits are scaled by 1/sqrt(d) (Section III-B writes the scale, III-A omits it);
-  * the attention of step t runs over the cache *including* the new token and
-    *before* compression (Algorithm 1 obtains A_t ahead of the capacity test);
-  * Algorithm 1 excludes only the newest token from the arg-min; the
-    recent window R generalises this to the R newest tokens (R=1 is the
-    algorithm verbatim; Section V-A keeps a recent region in its experiments);
-  * ties in the arg-min go to the oldest token;
-  * the survivor keeps its own key, score sum and count (Algorithm 1 removes
-    only index j).
+  * a step attends over the table *with* the incoming token and *before* anything is removed
+    (Algorithm 1 obtains the attention weights ahead of its capacity test);
+  * Algorithm 1 spares only the newest token from removal; `R` spares the R newest (R = 1 is
+    the algorithm as printed; Section V-A keeps a recent region), `n_sink` the first tokens;
+  * equal importance: the oldest token goes;
+  * the token that absorbs a value keeps its own key, mass and age (Algorithm 1 removes the
+    victim's entries only);
+  * both importances zero: the two values are averaged.
 
 Nothing on the product path may import this module.
 """
 import math
 
+AVERAGE, CUMULATIVE, LATEST = 0, 1, 2
+
+
+class Rec:
+    __slots__ = ("key", "value", "mass", "born", "folded", "latest")
+
+    def __init__(self, key, value, born):
+        self.key, self.value = list(key), list(value)
+        self.mass, self.born, self.folded, self.latest = 0.0, born, 1, 0.0
+
+
+def _softmax_weights(q, keys):
+    d = len(q)
+    logit = [math.fsum(qc * kc for qc, kc in zip(q, key)) / math.sqrt(d) for key in keys]
+    top = max(logit)
+    ex = [math.exp(x - top) for x in logit]
+    total = sum(ex)
+    return [x / total for x in ex]
+
 
 class BruteUnit:
-    def __init__(self, d, m, R, n_sink=0, merge=True, rounder=None):
+    def __init__(self, d, m, R, n_sink=0, merge=True, rounder=None, rule=AVERAGE):
         assert 1 <= R <= m and n_sink >= 0 and n_sink + R <= m
+        assert rule == AVERAGE or not merge          # the two other rules only evict
         self.d, self.m, self.R = d, m, R
-        self.n_sink, self.merge, self.rounder = n_sink, merge, rounder
-        self.K, self.V = [], []          # lists of d-lists
-        self.a, self.n = [], []          # score sums, counts   (Algorithm 1: the two lists)
-        self.pos, self.nmerged = [], []  # bookkeeping for tests only
-        self.t = 0
+        self.n_sink, self.merge, self.rounder, self.rule = n_sink, merge, rounder, rule
+        self.table = {}                  # token index -> Rec; insertion order is token order
+        self.t = 0                       # tokens seen
+
+    # ---- views in token order, shaped like the C oracle's state
+    def _recs(self):
+        return [self.table[tok] for tok in sorted(self.table)]
+
+    pos = property(lambda self: sorted(self.table))
+    K = property(lambda self: [r.key for r in self._recs()])
+    V = property(lambda self: [r.value for r in self._recs()])
+    a = property(lambda self: [r.mass for r in self._recs()])
+    n = property(lambda self: [self.t - r.born for r in self._recs()])     # steps attended so far
+    nmerged = property(lambda self: [r.folded for r in self._recs()])
+
+    def _importance(self, rec, now):
+        """How much a token matters when token `now` has just been attended."""
+        if self.rule == AVERAGE:
+            return rec.mass / (now - rec.born + 1)       # mass per step attended (Section IV)
+        if self.rule == CUMULATIVE:
+            return rec.mass                               # accumulated attention (Section II)
+        return rec.latest                                 # the latest step's weight (Section II)
+
+    def _shrink(self, now):
+        """Remove the least important unprotected token; returns (its rank, its index)."""
+        order = sorted(self.table)
+        free = order[self.n_sink:len(order) - self.R]
+        victim = min(free, key=lambda tok: (self._importance(self.table[tok], now), tok))
+        rank = order.index(victim)
+        if self.merge:
+            heir = self.table[order[rank + 1]]            # the next token in token order
+            gone = self.table[victim]
+            wg, wh = self._importance(gone, now), self._importance(heir, now)
+            if wg + wh > 0:
+                mixed = [(wg * x + wh * y) / (wg + wh) for x, y in zip(gone.value, heir.value)]
+            else:
+                mixed = [0.5 * x + 0.5 * y for x, y in zip(gone.value, heir.value)]
+            heir.value = mixed
+            heir.folded += gone.folded
+        del self.table[victim]
+        return rank, victim
 
     def step(self, q, k, v):
-        """Returns (o, evict_slot, evict_pos); evict_* are -1 when nothing was evicted."""
-        d = self.d
-        # K_t = [K_{t-1}, k_t], V_t = [V_{t-1}, v_t]            (Section III-A)
-        self.K.append(list(k)); self.V.append(list(v))
-        self.pos.append(self.t); self.nmerged.append(1)
-        L = len(self.K)
-        # A_t = softmax(q^T K_t / sqrt(d)),  o_t = A_t^T V_t    (Section III-A, III-B)
-        s = [sum(q[c] * self.K[i][c] for c in range(d)) / math.sqrt(d) for i in range(L)]
-        mx = max(s)
-        e = [math.exp(x - mx) for x in s]
-        S = sum(e)
-        A = [x / S for x in e]
-        o = [sum(A[i] * self.V[i][c] for i in range(L)) for c in range(d)]
-        # a = [a, 0] + A_t ; n = [n, 0] + 1                      (Algorithm 1: bookkeeping)
-        self.a = [x + y for x, y in zip(self.a + [0.0], A)]
-        self.n = [x + 1 for x in self.n + [0]]
-        ev_slot, ev_pos = -1, -1
-        if L > self.m:                                           # cache exceeds m
-            abar = [self.a[i] / self.n[i] for i in range(L)]     # average scores
-            cand = range(self.n_sink, L - self.R)                # arg-min outside protected regions
-            j = min(cand, key=lambda i: (abar[i], i))
-            if self.merge:                                       # convex merge
-                den = abar[j] + abar[j + 1]
-                if den > 0:
-                    merged = [(abar[j] * self.V[j][c] + abar[j + 1] * self.V[j + 1][c]) / den
-                              for c in range(d)]
-                else:
-                    merged = [0.5 * self.V[j][c] + 0.5 * self.V[j + 1][c] for c in range(d)]
-                if self.rounder is not None:
-                    merged = [self.rounder(x) for x in merged]
-                self.V[j + 1] = merged
-                self.nmerged[j + 1] += self.nmerged[j]
-            ev_slot, ev_pos = j, self.pos[j]
-            for lst in (self.K, self.V, self.a, self.n, self.pos, self.nmerged):  # removal
-                del lst[j]
+        """One generated token.  Returns (o, rank of the removed token, its index); -1, -1 when
+        nothing was removed."""
+        now = self.t
+        self.table[now] = Rec(k, v, now)
+        recs = self._recs()
+        w = _softmax_weights(q, [r.key for r in recs])                    # Section III-A
+        o = [sum(wi * r.value[c] for wi, r in zip(w, recs)) for c in range(self.d)]
+        for wi, r in zip(w, recs):                                        # Algorithm 1's bookkeeping
+            r.mass += wi
+            r.latest = wi
+        rank, victim = -1, -1
+        if len(self.table) > self.m:
+            rank, victim = self._shrink(now)
+            if self.merge and self.rounder is not None and rank < len(self.table):
+                heir = self._recs()[rank]
+                heir.value = [self.rounder(x) for x in heir.value]        # the row is stored
         self.t += 1
-        return o, ev_slot, ev_pos
+        return o, rank, victim
 
     def prefill(self, Q, Kp, Vp):
-        """Bulk prefill of the empty cache with a prompt (lists of d-lists).  Reading (the paper
-        has no such procedure): causal attention over the uncompressed prompt, the scores that
-        Algorithm 1's bookkeeping would accumulate over those rows, then selection and merge
-        repeated until m entries remain, with no attention in between; merged rows are rounded to
-        the cache format once, when the compression is over.
-        Returns (outputs, removed tokens in order)."""
-        assert self.t == 0
-        d, P = self.d, len(Q)
+        """A prompt given at once to the empty table (a reading: the paper streams).  Every
+        prompt token attends causally over the whole, uncompressed prompt and the masses add up
+        as in step(); then tokens are removed, by the same rule with the masses as they stand,
+        until m remain.  Values are rounded once, when the removal is over.  The latest-weight
+        rule has no meaning here.  Returns (outputs, removed tokens in order)."""
+        assert self.t == 0 and self.rule != LATEST
         outs = []
-        for t in range(P):
-            self.K.append(list(Kp[t])); self.V.append(list(Vp[t]))
-            self.pos.append(t); self.nmerged.append(1)
-            s = [sum(Q[t][c] * self.K[i][c] for c in range(d)) / math.sqrt(d) for i in range(t + 1)]
-            mx = max(s)
-            e = [math.exp(x - mx) for x in s]
-            S = sum(e)
-            A = [x / S for x in e]
-            outs.append([sum(A[i] * self.V[i][c] for i in range(t + 1)) for c in range(d)])
-            self.a = [x + y for x, y in zip(self.a + [0.0], A)]
-            self.n = [x + 1 for x in self.n + [0]]
+        for now, (q, k, v) in enumerate(zip(Q, Kp, Vp)):
+            self.table[now] = Rec(k, v, now)
+            recs = self._recs()
+            w = _softmax_weights(q, [r.key for r in recs])
+            outs.append([sum(wi * r.value[c] for wi, r in zip(w, recs)) for c in range(self.d)])
+            for wi, r in zip(w, recs):
+                r.mass += wi
+        last = len(Q) - 1
         removed = []
-        while len(self.K) > self.m:
-            L = len(self.K)
-            abar = [self.a[i] / self.n[i] for i in range(L)]
-            j = min(range(self.n_sink, L - self.R), key=lambda i: (abar[i], i))
-            if self.merge:
-                den = abar[j] + abar[j + 1]
-                merged = [(abar[j] * self.V[j][c] + abar[j + 1] * self.V[j + 1][c]) / den if den > 0
-                          else 0.5 * self.V[j][c] + 0.5 * self.V[j + 1][c] for c in range(d)]
-                self.V[j + 1] = merged                                   # not rounded: never stored as such
-                self.nmerged[j + 1] += self.nmerged[j]
-            removed.append(self.pos[j])
-            for lst in (self.K, self.V, self.a, self.n, self.pos, self.nmerged):
-                del lst[j]
-        if self.rounder is not None:                                     # rows enter the cache: one rounding
-            self.V = [[self.rounder(x) for x in row] for row in self.V]
-        self.t = P
+        while len(self.table) > self.m:
+            removed.append(self._shrink(last)[1])
+        if self.rounder is not None:
+            for r in self.table.values():
+                r.value = [self.rounder(x) for x in r.value]
+        self.t = len(Q)
         return outs, removed
