@@ -631,3 +631,21 @@ def test_streaming_after_prefill_continues_from_the_prefilled_state():
         np.testing.assert_allclose(r["out"][t - P, 0], ob, rtol=0, atol=1e-12)
         assert r["evict_pos"][t - P, 0] == ep
     assert o.state(0)["pos"].tolist() == b.pos and o.state(0)["n"].tolist() == b.n
+
+
+# ---------------------------------------------------------------------------
+# the single-merge perturbation experiment of Section IV (Fig. 2), on a synthetic stack
+# ---------------------------------------------------------------------------
+def test_single_merge_perturbation_diagnostic():
+    """What the mathematics fixes: before the merge the two runs are the same run (similarity 1);
+    in the first layer, whose queries and keys do not depend on earlier outputs, removing a key
+    rescales the other weights of a row by one common factor, so the similarity stays 1 after
+    the merge too; deeper layers see changed inputs and move, a little."""
+    from oracle import diagnostic
+    res = diagnostic.single_merge_perturbation(d=16, n_layers=3, merge_at=25, follow=90, seed=3)
+    for li, r in res.items():
+        assert abs(r["before"] - 1.0) <= 4e-16
+        assert r["std"] >= 0 and r["min"] <= r["mean"] <= 1.0 + 1e-15
+    assert abs(res[0]["mean"] - 1.0) <= 1e-14 and abs(res[0]["min"] - 1.0) <= 1e-14
+    for li in (1, 2):
+        assert 0.9 < res[li]["min"] < 1.0 - 1e-9          # perturbed, but still the same attention pattern
