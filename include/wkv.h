@@ -86,7 +86,9 @@ typedef struct wkv_options {
     int split;                   /* optional: workgroups per unit, 1/2/4/8/16; default: 1 unless   */
                                  /*   the units alone would leave most of the GPU idle             */
     int streaming;               /* optional: WKV_LOADS_*: how wkv_step loads the cached K/V rows  */
-    int reserved[3];             /* must be zero                                                   */
+    int max_prompt;              /* optional: prompt length (tokens) for which wkv_create_ex already */
+                                 /*   reserves wkv_prefill's scratch, so that the call allocates nothing */
+    int reserved[2];             /* must be zero                                                   */
 } wkv_options;
 
 /*
@@ -143,13 +145,31 @@ int wkv_step(wkv_handle* h, const void* q, const void* k_new, const void* v_new,
  *             dtype, 16-byte aligned, read only.
  *   out     : DEVICE pointer of the same shape, or NULL if the outputs are not wanted.
  * Built for 16-bit caches with head_dim 64 or 128 and the average or cumulative scoring rule
- * (WKV_ESIZE / WKV_EINVAL otherwise); 1 <= n_tokens <= WKV_MAX_PROMPT.  Allocates and frees its
- * own device scratch (16 bytes per token and unit)
- * and returns when the work on `stream` has completed.  The eviction log is not written.
- * On error the cache is unchanged, except for WKV_EHIP after the launch.
+ * (WKV_ESIZE / WKV_EINVAL otherwise); 1 <= n_tokens <= WKV_MAX_PROMPT.
+ * Asynchronous like wkv_step: returns after enqueueing three kernels on `stream`; the caller keeps
+ * q, k, v, out valid until the stream reaches them.  Device scratch (16 bytes per token and unit)
+ * belongs to the handle: reserved by wkv_create_ex when wkv_options.max_prompt covers n_tokens,
+ * otherwise allocated (and kept) by the first call that needs it -- only that call allocates.
+ * The eviction log is not written.  On error the cache is unchanged, except for WKV_EHIP after
+ * the launch.
  */
 int wkv_prefill(wkv_handle* h, const void* q, const void* k, const void* v, void* out,
                 int n_tokens, void* stream);
+
+/*
+ * wkv_prefill for callers that cannot allocate device memory at all: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernels,
+ * same results; the scratch is a static device array inside the library
+ * (WKV_NOALLOC_SCRATCH_BYTES, held by every GPU the library runs on until the process ends)
+ * instead of memory of the handle, so the call performs no allocation and no free, whatever
+ * wkv_options.max_prompt said.  Limit: batch*heads * n_tokens <= WKV_NOALLOC_SCRATCH_BYTES / 16
+ * (WKV_ESIZE beyond).  All calls on one GPU share the array: two such calls must not overlap in
+ * time (put them on one stream, or order them with events); nothing in it has to start at zero,
+ * every value read is written by the same call first.
+ */
+#define WKV_NOALLOC_SCRATCH_BYTES (16u << 20)   /* 256 units x 4096 tokens, or 1024 x 1024, ... */
+int wkv_prefill_noalloc(wkv_handle* h, const void* q, const void* k, const void* v, void* out,
+                        int n_tokens, void* stream);
 
 /* what wkv_state reads back */
 #define WKV_STEP       0  /* int64[1]            tokens processed so far                             */
@@ -205,6 +225,19 @@ size_t wkv_workspace_bytes(const wkv_options* opt);
  * read, q/k_new/v_new read, out written, the new K/V rows written, the merged
  * V row written.  Host-only arithmetic. */
 size_t wkv_step_bytes(const wkv_options* opt);
+
+/*
+ * Measurement aid, no part of the method: a plain streaming read of `bytes` bytes of DEVICE memory
+ * at `src` by `workgroups` workgroups of `threads` threads (64..1024, a multiple of 64), each
+ * workgroup its own contiguous share, 16 bytes per lane and load, four loads in flight per lane;
+ * non-temporal loads if `nontemporal` is non-zero.  Nothing is written (`sink`, 4 bytes of device
+ * memory or NULL, only keeps the loads alive).  Asynchronous on `stream`.  The benchmark times it
+ * with the grid and byte count of a wkv_step launch: what that launch shape can pull out of
+ * memory when it does nothing else.  `bytes` must be a positive multiple of 16*workgroups
+ * (WKV_EINVAL otherwise); the caller owns src and keeps it valid.
+ */
+int wkv_probe_read(const void* src, size_t bytes, int workgroups, int threads, int nontemporal,
+                   void* sink, void* stream);
 
 int wkv_version(void);
 

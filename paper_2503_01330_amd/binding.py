@@ -29,14 +29,14 @@ WKV_LOADS_AUTO, WKV_LOADS_CACHED, WKV_LOADS_STREAMING = 0, 1, 2
 (WKV_STEP, WKV_LEN, WKV_K, WKV_V, WKV_SCORE_SUM, WKV_COUNT, WKV_POS, WKV_NMERGED,
  WKV_EVICT_POS, WKV_EVICT_SLOT, WKV_STATUS) = range(11)
 
-EXPORTS = ("wkv_create", "wkv_create_ex", "wkv_step", "wkv_prefill", "wkv_state", "wkv_load", "wkv_destroy",
-           "wkv_last_error", "wkv_workspace_bytes", "wkv_step_bytes", "wkv_version")
+EXPORTS = ("wkv_create", "wkv_create_ex", "wkv_step", "wkv_prefill", "wkv_prefill_noalloc", "wkv_state", "wkv_load", "wkv_destroy",
+           "wkv_last_error", "wkv_workspace_bytes", "wkv_step_bytes", "wkv_probe_read", "wkv_version")
 
 
 class wkv_options(C.Structure):
     _fields_ = [(n, C.c_int) for n in ("batch", "heads", "head_dim", "budget", "recent_window",
                                         "dtype", "n_sink", "score_mode", "merge_mode",
-                                        "log_capacity", "threads", "split", "streaming")] + [("reserved", C.c_int * 3)]
+                                        "log_capacity", "threads", "split", "streaming", "max_prompt")] + [("reserved", C.c_int * 2)]
 
 
 class WkvError(RuntimeError):
@@ -54,6 +54,7 @@ _lib.wkv_create.argtypes = [C.POINTER(C.c_void_p)] + [C.c_int] * 6
 _lib.wkv_create_ex.argtypes = [C.POINTER(C.c_void_p), C.POINTER(wkv_options)]
 _lib.wkv_step.argtypes = [C.c_void_p] * 6
 _lib.wkv_prefill.argtypes = [C.c_void_p] * 5 + [C.c_int, C.c_void_p]
+_lib.wkv_prefill_noalloc.argtypes = [C.c_void_p] * 5 + [C.c_int, C.c_void_p]
 _lib.wkv_state.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.c_size_t]
 _lib.wkv_load.argtypes = [C.c_void_p, C.c_int64, C.c_int] + [C.c_void_p] * 4
 _lib.wkv_destroy.argtypes = [C.c_void_p]
@@ -62,6 +63,15 @@ _lib.wkv_workspace_bytes.restype = C.c_size_t
 _lib.wkv_workspace_bytes.argtypes = [C.POINTER(wkv_options)]
 _lib.wkv_step_bytes.restype = C.c_size_t
 _lib.wkv_step_bytes.argtypes = [C.POINTER(wkv_options)]
+
+
+_lib.wkv_probe_read.argtypes = [C.c_void_p, C.c_size_t, C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_void_p]
+
+
+def wkv_probe_read(src: int, nbytes: int, workgroups: int, threads: int, nontemporal: bool, sink: int = 0,
+                   stream: int = 0) -> None:
+    """Plain streaming read of device memory with a chosen launch shape (measurement aid)."""
+    _check(_lib.wkv_probe_read(src, nbytes, workgroups, threads, int(nontemporal), sink or None, stream))
 
 
 def wkv_last_error() -> str:
@@ -78,9 +88,9 @@ def wkv_version() -> int:
 
 
 def make_options(batch, heads, head_dim, budget, recent_window, dtype, n_sink=0, score_mode=0,
-                 merge_mode=0, log_capacity=0, threads=0, split=0, streaming=0) -> wkv_options:
+                 merge_mode=0, log_capacity=0, threads=0, split=0, streaming=0, max_prompt=0) -> wkv_options:
     return wkv_options(batch, heads, head_dim, budget, recent_window, dtype, n_sink, score_mode,
-                       merge_mode, log_capacity, threads, split, streaming)
+                       merge_mode, log_capacity, threads, split, streaming, max_prompt)
 
 
 def wkv_create(batch, heads, head_dim, budget, recent_window, dtype):
@@ -103,6 +113,11 @@ def wkv_step(h, q: int, k_new: int, v_new: int, out: int, stream: int = 0) -> No
 def wkv_prefill(h, q: int, k: int, v: int, out: int, n_tokens: int, stream: int = 0) -> None:
     """q, k, v, out: device addresses of [n_tokens, batch, heads, head_dim] arrays (out may be 0)."""
     _check(_lib.wkv_prefill(h, q, k, v, out or None, n_tokens, stream))
+
+
+def wkv_prefill_noalloc(h, q: int, k: int, v: int, out: int, n_tokens: int, stream: int = 0) -> None:
+    """wkv_prefill on the library's static scratch: no device allocation in the call."""
+    _check(_lib.wkv_prefill_noalloc(h, q, k, v, out or None, n_tokens, stream))
 
 
 def wkv_state_raw(h, what: int, dst: np.ndarray) -> None:
@@ -149,14 +164,15 @@ class Cache:
             stream = torch.cuda.current_stream().cuda_stream
         wkv_step(self.h, q.data_ptr(), k_new.data_ptr(), v_new.data_ptr(), out.data_ptr(), stream)
 
-    def prefill(self, q, k, v, out=None, stream=None):
+    def prefill(self, q, k, v, out=None, stream=None, noalloc=False):
         """q, k, v (and out, if wanted): torch tensors on the GPU, contiguous [n_tokens, batch, heads, head_dim]
-        (or [n_tokens, units, head_dim]); the cache must be empty."""
+        (or [n_tokens, units, head_dim]); the cache must be empty.  noalloc: through wkv_prefill_noalloc."""
         if stream is None:
             import torch
             stream = torch.cuda.current_stream().cuda_stream
-        wkv_prefill(self.h, q.data_ptr(), k.data_ptr(), v.data_ptr(), out.data_ptr() if out is not None else 0,
-                    q.shape[0], stream)
+        (wkv_prefill_noalloc if noalloc else wkv_prefill)(
+            self.h, q.data_ptr(), k.data_ptr(), v.data_ptr(), out.data_ptr() if out is not None else 0,
+            q.shape[0], stream)
 
     def step_ptr(self, q, k_new, v_new, out, stream=0):
         wkv_step(self.h, q, k_new, v_new, out, stream)

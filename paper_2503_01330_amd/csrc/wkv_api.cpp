@@ -77,6 +77,9 @@ int validate(const wkv_options& o, int* threads, int* split)
         return fail(WKV_EINVAL, "cumulative / last-step scoring are eviction rules: use WKV_MERGE_NONE");
     if (o.log_capacity < 0) return fail(WKV_EINVAL, "log_capacity must be >= 0");
     if (o.streaming < 0 || o.streaming > 2) return fail(WKV_EINVAL, "streaming must be WKV_LOADS_AUTO, _CACHED or _STREAMING");
+    if (o.max_prompt < 0 || o.max_prompt > WKV_MAX_PROMPT) return fail(WKV_EINVAL, "max_prompt must be in 0..WKV_MAX_PROMPT");
+    if (o.max_prompt > 0 && (o.dtype == WKV_FP32 || o.head_dim > 128))
+        return fail(WKV_ESIZE, "max_prompt: wkv_prefill is built for 16-bit caches with head_dim 64 or 128");
     for (int r : o.reserved) if (r != 0) return fail(WKV_EINVAL, "reserved fields must be zero");
     int th = o.threads, sp = o.split;
     const int units = o.batch * o.heads;
@@ -143,7 +146,9 @@ Sizes sizes(const wkv_options& o, int split)
     s.po = split > 1 ? units * split * o.head_dim * sizeof(double) : 0;
     s.ps = split > 1 ? units * split * sizeof(double) : 0;
     s.cnt = split > 1 ? units * sizeof(uint32_t) : 0;
-    s.total = 2 * s.kv + s.a + 2 * s.i32 + 2 * s.log + s.status + s.lg + s.po + 3 * s.ps + s.cnt;
+    // wkv_prefill's scratch, when reserved at creation
+    const size_t pf = 2 * units * (size_t)(o.max_prompt > 0 ? o.max_prompt : 0) * sizeof(double);
+    s.total = 2 * s.kv + s.a + 2 * s.i32 + 2 * s.log + s.status + s.lg + s.po + 3 * s.ps + s.cnt + pf;
     return s;
 }
 
@@ -157,6 +162,8 @@ struct wkv_handle {
     int threads;
     int64_t t;        // tokens processed
     int64_t log_from; // first step whose eviction log entry is valid (after wkv_load)
+    double* pf_scratch;  // wkv_prefill's scratch: [2][units][pf_tokens] fp64, or null
+    int pf_tokens;
 };
 
 namespace {
@@ -168,6 +175,54 @@ int on_device(const wkv_handle* h)
     const hipError_t e = hipGetDevice(&dev);
     if (e != hipSuccess) return fail(WKV_EHIP, "hipGetDevice: %s", hipGetErrorString(e));
     if (dev != h->device) return fail(WKV_EINVAL, "handle belongs to device %d, current device is %d", h->device, dev);
+    return WKV_OK;
+}
+
+// Argument checks shared by the two prefill entry points; nothing is launched or allocated here.
+int prefill_check(wkv_handle* h, const void* q, const void* k, const void* v, void* out, int n_tokens)
+{
+    if (!h) return fail(WKV_EINVAL, "null handle");
+    if (!q || !k || !v) return fail(WKV_EINVAL, "null device pointer");
+    if ((((uintptr_t)q | (uintptr_t)k | (uintptr_t)v | (uintptr_t)out) & 15) != 0)
+        return fail(WKV_EINVAL, "q, k, v and out must be 16-byte aligned");
+    if (h->t != 0) return fail(WKV_EINVAL, "wkv_prefill needs an empty cache (%lld tokens processed)", (long long)h->t);
+    if (n_tokens < 1) return fail(WKV_EINVAL, "n_tokens must be positive");
+    if (n_tokens > WKV_MAX_PROMPT) return fail(WKV_ESIZE, "n_tokens %d exceeds WKV_MAX_PROMPT %d", n_tokens, WKV_MAX_PROMPT);
+    const wkv_options& o = h->opt;
+    if (o.dtype == WKV_FP32 || o.head_dim > 128)
+        return fail(WKV_ESIZE, "wkv_prefill is built for 16-bit caches with head_dim 64 or 128");
+    if (o.score_mode == WKV_SCORE_LAST)
+        return fail(WKV_EINVAL, "the last-step scoring rule is not defined for a prompt");
+    const int rc = on_device(h);
+    if (rc != WKV_OK) return rc;
+    int lds_max = 0;
+    const hipError_t e = hipDeviceGetAttribute(&lds_max, hipDeviceAttributeMaxSharedMemoryPerBlock, h->device);
+    if (e == hipSuccess && wkv_prefill_lds_bytes(n_tokens) > (size_t)lds_max)
+        return fail(WKV_ESIZE, "a prompt of %d tokens needs %zu bytes of LDS, the device offers %d", n_tokens,
+                    wkv_prefill_lds_bytes(n_tokens), lds_max);
+    return WKV_OK;
+}
+
+// The handle's own prefill scratch (row log-sum-exps and column sums, fp64 each): sized for
+// `tokens` prompt tokens, grown when a longer prompt comes, freed by wkv_destroy.
+int prefill_reserve(wkv_handle* h, int tokens)
+{
+    if (tokens <= h->pf_tokens) return WKV_OK;
+    const size_t n = (size_t)h->c.units * (size_t)tokens * sizeof(double);
+    double* p = nullptr;
+    const hipError_t e = hipMalloc((void**)&p, 2 * n);
+    if (e != hipSuccess) {
+        (void)hipGetLastError();
+        return fail(e == hipErrorOutOfMemory ? WKV_ENOMEM : WKV_EHIP, "scratch for a prompt of %d tokens: %s",
+                    tokens, hipGetErrorString(e));
+    }
+    if (h->pf_scratch) {
+        // an earlier, shorter prompt's kernels may still be reading the old block
+        (void)hipDeviceSynchronize();
+        (void)hipFree(h->pf_scratch);
+    }
+    h->pf_scratch = p;
+    h->pf_tokens = tokens;
     return WKV_OK;
 }
 
@@ -212,6 +267,8 @@ int wkv_create_ex(wkv_handle** hp, const wkv_options* opt)
     h->threads = threads;
     h->t = 0;
     h->log_from = 0;
+    h->pf_scratch = nullptr;
+    h->pf_tokens = 0;
     hipError_t e = hipGetDevice(&h->device);
     if (e != hipSuccess) {
         delete h;
@@ -266,6 +323,14 @@ int wkv_create_ex(wkv_handle** hp, const wkv_options* opt)
             return rc;
         }
     }
+    if (opt->max_prompt > 0) {
+        rc = prefill_reserve(h, opt->max_prompt);
+        if (rc != WKV_OK) {
+            for (auto& b2 : bufs) if (*b2.p) (void)hipFree(*b2.p);
+            delete h;
+            return rc;
+        }
+    }
     count_live(h->device, 2 * (long long)s.kv);
     *hp = h;
     return WKV_OK;
@@ -302,41 +367,36 @@ int wkv_step(wkv_handle* h, const void* q, const void* k_new, const void* v_new,
 int wkv_prefill(wkv_handle* h, const void* q, const void* k, const void* v, void* out, int n_tokens,
                 void* stream)
 {
-    if (!h) return fail(WKV_EINVAL, "null handle");
-    if (!q || !k || !v) return fail(WKV_EINVAL, "null device pointer");
-    if ((((uintptr_t)q | (uintptr_t)k | (uintptr_t)v | (uintptr_t)out) & 15) != 0)
-        return fail(WKV_EINVAL, "q, k, v and out must be 16-byte aligned");
-    if (h->t != 0) return fail(WKV_EINVAL, "wkv_prefill needs an empty cache (%lld tokens processed)", (long long)h->t);
-    if (n_tokens < 1) return fail(WKV_EINVAL, "n_tokens must be positive");
-    if (n_tokens > WKV_MAX_PROMPT) return fail(WKV_ESIZE, "n_tokens %d exceeds WKV_MAX_PROMPT %d", n_tokens, WKV_MAX_PROMPT);
-    const wkv_options& o = h->opt;
-    if (o.dtype == WKV_FP32 || o.head_dim > 128)
-        return fail(WKV_ESIZE, "wkv_prefill is built for 16-bit caches with head_dim 64 or 128");
-    if (o.score_mode == WKV_SCORE_LAST)
-        return fail(WKV_EINVAL, "the last-step scoring rule is not defined for a prompt");
-    const int rc = on_device(h);
+    int rc = prefill_check(h, q, k, v, out, n_tokens);
     if (rc != WKV_OK) return rc;
-    int lds_max = 0;
-    hipError_t e = hipDeviceGetAttribute(&lds_max, hipDeviceAttributeMaxSharedMemoryPerBlock, h->device);
-    if (e == hipSuccess && wkv_prefill_lds_bytes(n_tokens) > (size_t)lds_max)
-        return fail(WKV_ESIZE, "a prompt of %d tokens needs %zu bytes of LDS, the device offers %d", n_tokens,
-                    wkv_prefill_lds_bytes(n_tokens), lds_max);
-
-    const size_t units = h->c.units, P = (size_t)n_tokens;
-    double *lse = nullptr, *a = nullptr;
-    e = hipMalloc((void**)&lse, units * P * sizeof(double));
-    if (e == hipSuccess) e = hipMalloc((void**)&a, units * P * sizeof(double));
-    if (e != hipSuccess) {
-        (void)hipGetLastError();
-        if (lse) (void)hipFree(lse);
-        return fail(e == hipErrorOutOfMemory ? WKV_ENOMEM : WKV_EHIP, "scratch for a prompt of %d tokens: %s",
-                    n_tokens, hipGetErrorString(e));
-    }
-    e = wkv_launch_prefill(h->c, o.dtype, o.head_dim, q, k, v, out, lse, a, n_tokens, (hipStream_t)stream);
-    const hipError_t e2 = hipStreamSynchronize((hipStream_t)stream);
-    (void)hipFree(lse); (void)hipFree(a);
+    rc = prefill_reserve(h, n_tokens);
+    if (rc != WKV_OK) return rc;
+    double* lse = h->pf_scratch;
+    double* a = lse + (size_t)h->c.units * (size_t)n_tokens;
+    const hipError_t e = wkv_launch_prefill(h->c, h->opt.dtype, h->opt.head_dim, q, k, v, out, lse, a, n_tokens,
+                                            (hipStream_t)stream);
     if (e != hipSuccess) return fail(WKV_EHIP, "kernel launch: %s", hipGetErrorString(e));
-    if (e2 != hipSuccess) return fail(WKV_EHIP, "hipStreamSynchronize: %s", hipGetErrorString(e2));
+    h->t = n_tokens;
+    h->log_from = n_tokens;
+    return WKV_OK;
+}
+
+int wkv_prefill_noalloc(wkv_handle* h, const void* q, const void* k, const void* v, void* out, int n_tokens,
+                        void* stream)
+{
+    int rc = prefill_check(h, q, k, v, out, n_tokens);
+    if (rc != WKV_OK) return rc;
+    const size_t need = 2 * (size_t)h->c.units * (size_t)n_tokens * sizeof(double);
+    if (need > WKV_NOALLOC_SCRATCH_BYTES)
+        return fail(WKV_ESIZE, "units x n_tokens = %zu exceeds the %zu the static scratch of wkv_prefill_noalloc holds",
+                    (size_t)h->c.units * (size_t)n_tokens, (size_t)WKV_NOALLOC_SCRATCH_BYTES / 16);
+    double* base = nullptr;
+    hipError_t e = wkv_prefill_static_scratch(h->device, &base);
+    if (e != hipSuccess) return fail(WKV_EHIP, "address of the static scratch: %s", hipGetErrorString(e));
+    double* lse = base;
+    double* a = lse + (size_t)h->c.units * (size_t)n_tokens;
+    e = wkv_launch_prefill(h->c, h->opt.dtype, h->opt.head_dim, q, k, v, out, lse, a, n_tokens, (hipStream_t)stream);
+    if (e != hipSuccess) return fail(WKV_EHIP, "kernel launch: %s", hipGetErrorString(e));
     h->t = n_tokens;
     h->log_from = n_tokens;
     return WKV_OK;
@@ -519,6 +579,19 @@ int wkv_load(wkv_handle* h, int64_t tokens, int len, const void* K, const void* 
     }
 }
 
+int wkv_probe_read(const void* src, size_t bytes, int workgroups, int threads, int nontemporal, void* sink, void* stream)
+{
+    if (!src) return fail(WKV_EINVAL, "null device pointer");
+    if (((uintptr_t)src & 15) != 0) return fail(WKV_EINVAL, "src must be 16-byte aligned");
+    if (workgroups < 1 || threads < 64 || threads > 1024 || threads % 64 != 0)
+        return fail(WKV_EINVAL, "workgroups must be positive, threads a multiple of 64 in 64..1024");
+    if (bytes == 0 || bytes % (16 * (size_t)workgroups) != 0)
+        return fail(WKV_EINVAL, "bytes must be a positive multiple of 16*workgroups");
+    const hipError_t e = wkv_launch_probe_read(src, bytes, workgroups, threads, nontemporal != 0, sink, (hipStream_t)stream);
+    if (e != hipSuccess) return fail(WKV_EHIP, "kernel launch: %s", hipGetErrorString(e));
+    return WKV_OK;
+}
+
 int wkv_destroy(wkv_handle* h)
 {
     if (!h) return WKV_OK;
@@ -530,6 +603,7 @@ int wkv_destroy(wkv_handle* h)
     void* bufs[] = { c.K, c.V, c.a, c.pos, c.nxt, c.log_pos, c.log_slot, c.status,
                      h->sp.lg, h->sp.po, h->sp.pm, h->sp.pl, h->sp.pe, h->sp.cnt };
     for (void* b : bufs) if (b) (void)hipFree(b);
+    if (h->pf_scratch) (void)hipFree(h->pf_scratch);
     count_live(h->device, -2 * (long long)sizes(h->opt, h->sp.S).kv);
     if (moved) (void)hipSetDevice(cur);
     delete h;

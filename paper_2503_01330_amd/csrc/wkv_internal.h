@@ -79,4 +79,14 @@ hipError_t wkv_launch_prefill(const WkvCache& c, int dtype, int head_dim, const 
                               const void* v, void* out, double* lse, double* a, int P, hipStream_t stream);
 size_t wkv_prefill_lds_bytes(int P);
 
+// Device address of the library's static prefill scratch (WKV_NOALLOC_SCRATCH_BYTES, declared in
+// wkv_prefill.hip) on `device`, which must be the current device.  Looked up once per device.
+hipError_t wkv_prefill_static_scratch(int device, double** ptr);
+
+
+// ---- measurement aid (wkv_probe.hip): `workgroups` x `threads` read `bytes` of device memory,
+// each workgroup its own contiguous share, and do nothing else.
+hipError_t wkv_launch_probe_read(const void* src, size_t bytes, int workgroups, int threads, bool nontemporal,
+                                 void* sink, hipStream_t stream);
+
 #endif

@@ -34,7 +34,9 @@
 //   result as f32 16x16x4.
 // The reduction index of a contraction may be permuted at will as long as A and B agree, so a lane
 // simply takes a contiguous quarter of its row: MFMA step kk uses element g*(D/4) + kk of both.
+#include "../../include/wkv.h"
 #include "wkv_internal.h"
+#include <mutex>
 #include "wkv_device.h"
 
 namespace {
@@ -725,6 +727,29 @@ hipError_t run(const WkvCache& c, const void* q, const void* k, const void* v, v
 }  // namespace
 
 size_t wkv_prefill_lds_bytes(int P) { return (size_t)P * 34 + 1024 * 4 + 64 * 2; }
+
+// ---- scratch of wkv_prefill_noalloc: a static device array, so that the call allocates nothing.
+// Every GPU holds its own copy at its own address; in host code the array's name is only a
+// stand-in for hipGetSymbolAddress, never an address to hand to a kernel.
+static __device__ __align__(256) unsigned char wkv_noalloc_scratch[WKV_NOALLOC_SCRATCH_BYTES];
+
+hipError_t wkv_prefill_static_scratch(int device, double** ptr)
+{
+    constexpr int MAX_DEVICES = 64;
+    static std::mutex mu;
+    static void* addr[MAX_DEVICES] = {};
+    if (device < 0 || device >= MAX_DEVICES) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(mu);
+    if (!addr[device]) {
+        void* p = nullptr;
+        const hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(wkv_noalloc_scratch));
+        if (e != hipSuccess) return e;
+        if (!p) return hipErrorInvalidSymbol;
+        addr[device] = p;
+    }
+    *ptr = static_cast<double*>(addr[device]);
+    return hipSuccess;
+}
 
 hipError_t wkv_launch_prefill(const WkvCache& c, int dtype, int head_dim, const void* q, const void* k,
                               const void* v, void* out, double* lse, double* a, int P, hipStream_t stream)

@@ -1,8 +1,8 @@
 """GPU parity: libwkv (through the C ABI) against the CPU oracle, element by element.
 
-Small cases compare every unit and the final cache state; the full-size
-configurations run the GPU on every unit in the launch configuration the
-benchmark uses and compare a sample of units that the oracle can afford.
+Every case compares every unit and the final cache state.  The full-size configurations
+(cfg3: three of its 32 layers, cfg4, cfg5) run in the launch configuration the benchmark uses
+and are compared chunk by chunk, so that no stream has to be held in memory.
 """
 import numpy as np
 import pytest
@@ -203,34 +203,33 @@ def test_cfg2_llama_layer_full_stream():
     assert stats["near_ties"] == 0
 
 
-def test_cfg3_stack_sampled_layers_and_units():
-    """Two of the 32 layers (first and last), full 4096-token stream on all 256 units in
-    the benchmark's launch shape; 6 sampled units per layer go through the oracle."""
-    cfg = synth.CONFIGS["cfg3"]
-    for layer in (0, 31):
-        sel = np.random.default_rng(layer).choice(cfg.units, 6, replace=False)
-        stats = _run(cfg, units_sel=np.sort(sel), layer=layer, label=f"cfg3 layer {layer}", split=0)
-        assert stats["near_ties"] == 0
+def _full(cfg, label, layer=0, **kw):
+    """Every unit of a full-size configuration against the oracle, in the launch shape the benchmark
+    times.  A disagreement within the near-tie threshold is logged and followed, not failed; the
+    count is printed."""
+    stats = parity.stream_compare(cfg, layer=layer, progress=label, **kw)
+    pos = stats.pop("pos")
+    print(f"\n  {label}: all {cfg.units} units x {cfg.steps} steps: {stats}", flush=True)
+    return stats, pos
 
 
-def test_cfg4_long_stream_sampled_units():
+@pytest.mark.parametrize("layer", [0, 15, 31])
+def test_cfg3_stack_every_unit_of_three_layers(layer):
+    """Layers 0, 15 and 31 of the 32-layer stack: the full 4096-token stream, all 256 units through
+    the oracle, with the non-temporal row loads the library uses when all 32 layers are live (the
+    instantiation the benchmark times)."""
+    _full(synth.CONFIGS["cfg3"], f"cfg3 layer {layer}", layer=layer, streaming=wkv.WKV_LOADS_STREAMING)
+
+
+def test_cfg4_long_stream_every_unit():
     cfg = synth.CONFIGS["cfg4"]
-    sel = np.array([0, 37, 90, 127])
-    g = parity.gpu_stream(cfg, units_sel=sel, progress="cfg4", split=0)   # as benchmarked: 2 workgroups per unit
-    try:
-        stats = parity.compare(cfg, g)
-        pos = g["cache"].state(wkv.WKV_POS)
-    finally:
-        g["cache"].close()
-    print(f"\n  cfg4: {stats}", flush=True)
-    # attention-sink heavy hitters (keys with 8x norm) survive by score alone
+    stats, pos = _full(cfg, "cfg4")                          # as benchmarked: the library picks 2 workgroups per unit
+    # attention-sink heavy hitters (keys with 8x norm) survive by score alone, in every unit
     assert (pos[:, :4] == np.arange(4)).all()
 
 
-def test_cfg5_batched_bf16_sampled_units():
-    cfg = synth.CONFIGS["cfg5"]
-    sel = np.sort(np.random.default_rng(5).choice(cfg.units, 8, replace=False))
-    _run(cfg, units_sel=sel, label="cfg5", split=0)
+def test_cfg5_batched_bf16_every_unit():
+    _full(synth.CONFIGS["cfg5"], "cfg5")
 
 
 @pytest.mark.parametrize("dtype,d,batch", [("fp16", 128, 64), ("fp32", 64, 64), ("bf16", 64, 128), ("bf16", 256, 32)])
