@@ -226,6 +226,11 @@ size_t wkv_workspace_bytes(const wkv_options* opt);
  * V row written.  Host-only arithmetic. */
 size_t wkv_step_bytes(const wkv_options* opt);
 
+/* The launch shape wkv_step uses for these options: *workgroups = units x workgroups per unit,
+ * *threads = threads per workgroup.  Host-only arithmetic.  WKV_OK, or the code wkv_create_ex
+ * would return for these options. */
+int wkv_launch_shape(const wkv_options* opt, int* workgroups, int* threads);
+
 /*
  * Measurement aid, no part of the method: a plain streaming read of `bytes` bytes of DEVICE memory
  * at `src` by `workgroups` workgroups of `threads` threads (64..1024, a multiple of 64), each

@@ -30,7 +30,7 @@ WKV_LOADS_AUTO, WKV_LOADS_CACHED, WKV_LOADS_STREAMING = 0, 1, 2
  WKV_EVICT_POS, WKV_EVICT_SLOT, WKV_STATUS) = range(11)
 
 EXPORTS = ("wkv_create", "wkv_create_ex", "wkv_step", "wkv_prefill", "wkv_prefill_noalloc", "wkv_state", "wkv_load", "wkv_destroy",
-           "wkv_last_error", "wkv_workspace_bytes", "wkv_step_bytes", "wkv_probe_read", "wkv_version")
+           "wkv_last_error", "wkv_workspace_bytes", "wkv_step_bytes", "wkv_launch_shape", "wkv_probe_read", "wkv_version")
 
 
 class wkv_options(C.Structure):
@@ -144,6 +144,13 @@ def wkv_workspace_bytes(opt: wkv_options) -> int:
 
 def wkv_step_bytes(opt: wkv_options) -> int:
     return _lib.wkv_step_bytes(C.byref(opt))
+
+
+def wkv_launch_shape(opt: wkv_options):
+    """(workgroups, threads per workgroup) of a wkv_step launch for these options."""
+    g, t = C.c_int(), C.c_int()
+    _check(_lib.wkv_launch_shape(C.byref(opt), C.byref(g), C.byref(t)))
+    return g.value, t.value
 
 
 _NP_STORE = {WKV_FP32: np.float32, WKV_FP16: np.float16, WKV_BF16: np.uint16}

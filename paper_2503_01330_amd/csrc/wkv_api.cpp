@@ -254,6 +254,17 @@ size_t wkv_step_bytes(const wkv_options* opt)
     return units * (L * (2 * row + 16 + 4) + 4 * row + 2 * row + 1 * row);
 }
 
+int wkv_launch_shape(const wkv_options* opt, int* workgroups, int* threads)
+{
+    if (!opt || !workgroups || !threads) return fail(WKV_EINVAL, "null argument");
+    int th, sp;
+    const int rc = validate(*opt, &th, &sp);
+    if (rc != WKV_OK) return rc;
+    *workgroups = opt->batch * opt->heads * sp;
+    *threads = th;
+    return WKV_OK;
+}
+
 int wkv_create_ex(wkv_handle** hp, const wkv_options* opt)
 {
     if (!hp || !opt) return fail(WKV_EINVAL, "null argument");
