@@ -86,9 +86,19 @@ void wkv_step_kernel(WkvCache c, const void* __restrict__ q_, const void* __rest
                      const void* __restrict__ v_, void* __restrict__ out_, int t)
 {
     using S = typename TT::soft_t;
-    // wave 0 also ranks the victim for the log: in the 1024-thread workgroups, and in smaller ones
-    // with a dedicated wave when the launch is small (uniform over the launch)
-    const bool RANK0 = DED && (MAXT > 512 || gridDim.x <= 768);
+    // QUAD (the 1024-thread workgroups, one per compute unit): Algorithm 1's bookkeeping is shared by
+    // four waves, one on each SIMD of the compute unit, which stream V like everybody else.  A wave
+    // issues one instruction every four cycles at best, whatever the instruction, and the
+    // bookkeeping of 411 entries is ~600 of them in a chain: 2.6 us in one wave, measured, with
+    // the rest of the workgroup waiting at the second barrier for the last microsecond of it.
+    // Four waves on four SIMDs take a quarter of the entries each; waves 1..3 publish their best
+    // candidate through LDS and wave 0, after a short wait on an LDS counter, picks among the four.
+    constexpr bool QUAD = MAXT > 512;
+    constexpr int NBK = QUAD ? 4 : 1;            // waves that keep the books
+    static_assert(!(QUAD && DED), "the four bookkeeping waves stream V too");
+    // wave 0 also ranks the victim for the log: in small launches with a dedicated wave (uniform
+    // over the launch); with four bookkeeping waves, wave 1 does it after the second barrier
+    const bool RANK0 = DED && gridDim.x <= 768;
     constexpr int EPL  = D / ROW_LANES;          // elements of a row per lane
     constexpr int NW32 = EPL * TT::BYTES / 4;    // 32-bit words per lane per row
     constexpr int ROWB = D * TT::BYTES;          // bytes per row
@@ -133,7 +143,8 @@ void wkv_step_kernel(WkvCache c, const void* __restrict__ q_, const void* __rest
     const int tail_blocks_v = (Ls - nfull_v * RBv + BR - 1) / BR;
     // the partial round of V goes to the V waves in order -- but to wave 0 last when it streams V
     // too: it has the bookkeeping to do first (2048 units x 410 slots: 77.6 -> 76.3 us per step)
-    const int vtail = DED ? vwid : (wid == 0 ? NW - 1 : wid - 1);
+    // (with four bookkeeping waves: to those four last)
+    const int vtail = QUAD ? (wid < NBK ? NW - NBK + wid : wid - NBK) : DED ? vwid : (wid == 0 ? NW - 1 : wid - 1);
     const bool in_tail_v = has_v && vtail < tail_blocks_v;
     const int nrounds_v = nfull_v + (in_tail_v ? 1 : 0);
     const int wv_in = (Lc % RBv) / BR;
@@ -168,25 +179,35 @@ void wkv_step_kernel(WkvCache c, const void* __restrict__ q_, const void* __rest
     // Thread tid owns entries tid, tid + NT, ... for staging and write-back.
     uint32_t qw[NW32];
     load_words<NW32>(qu + sub * LANEB, qw);
-    double a_reg[MAXPT];
-    int pos_reg[MAXPT], nxt_reg[MAXPT];
+    // A wave whose 64 entries of a round all lie beyond the cache skips that round's loads (a scalar
+    // condition; with 411 entries and 1024 threads that is nine waves of sixteen in the first round
+    // and everybody in the other three -- requests that would all have fetched slot 0).  These
+    // conditions sit ahead of the first row request, where they cost nothing: a request under a
+    // condition spoils the waits for requests that are OLDER than it, and nothing older is waited
+    // for separately (rows are younger, and waiting for a row waits for everything before it).
+    double a_reg[MAXPT] = {};
+    int pos_reg[MAXPT] = {}, nxt_reg[MAXPT] = {};
 #pragma unroll
     for (int k = 0; k < MAXPT; ++k) {
-        const int i = tid + k * NT;
-        const int ic = (i < Lc) ? i : 0;                   // slot 0 always exists in memory
-        a_reg[k] = au[ic];
-        pos_reg[k] = pu[ic];
-        nxt_reg[k] = nu[ic];
+        if (k * NT + wid * 64 < Lc) {
+            const int i = tid + k * NT;
+            const int ic = (i < Lc) ? i : 0;               // slot 0 always exists in memory
+            a_reg[k] = au[ic];
+            pos_reg[k] = pu[ic];
+            nxt_reg[k] = nu[ic];
+        }
     }
-    uint32_t knew_b[EPW], vnew_b[EPW];                     // the incoming row (raw), used by wave 0's write-back
+    uint32_t knew_b[EPW] = {}, vnew_b[EPW] = {};           // the incoming row (raw), for wave 0's write-back
+    if (wid == 0) {
 #pragma unroll
-    for (int e = 0; e < EPW; ++e) {
-        const int col = (lane + 64 * e < D) ? lane + 64 * e : 0;
-        knew_b[e] = load_bits<TT>(ku, col);
-        vnew_b[e] = load_bits<TT>(vu, col);
+        for (int e = 0; e < EPW; ++e) {
+            const int col = (lane + 64 * e < D) ? lane + 64 * e : 0;
+            knew_b[e] = load_bits<TT>(ku, col);
+            vnew_b[e] = load_bits<TT>(vu, col);
+        }
     }
-    [[maybe_unused]] uint32_t kin[NW32];                    // SEP: the incoming key in row layout
-    if constexpr (SEP) load_words<NW32>(ku + sub * LANEB, kin);
+    [[maybe_unused]] uint32_t kin[NW32] = {};               // SEP: the incoming key in row layout
+    if constexpr (SEP) { if (own_in) load_words<NW32>(ku + sub * LANEB, kin); }
 
     // ---- row requests.  Round r of a matrix: entries row_base + uu * row_stride, uu < U.
     uint32_t kw[U][NW32], vw[U][NW32];
@@ -262,7 +283,8 @@ void wkv_step_kernel(WkvCache c, const void* __restrict__ q_, const void* __rest
         if (r < nrounds) logits(r);
     }
     [[maybe_unused]] uint32_t vin[NW32];                    // SEP: the incoming value in row layout
-    if constexpr (SEP) load_words<NW32>(vu + sub * LANEB, vin);
+    if constexpr (SEP) load_words<NW32>(vu + sub * LANEB, vin);   // (by every wave: a condition here, between the
+                                                                  //  K requests and their use, would spoil the waits)
     // stage what the bookkeeping needs (these loads are older than the K rows: they have
     // arrived): score sums, token indices, and token order as a linked list (nl[i] = entry that
     // follows entry i; the newest cached token is followed by the incoming one, entry Lc)
@@ -272,7 +294,7 @@ void wkv_step_kernel(WkvCache c, const void* __restrict__ q_, const void* __rest
         if (i < Lc) { al[i] = a_reg[k]; pl[i] = pos_reg[k]; nl[i] = (nxt_reg[k] < 0) ? Lc : nxt_reg[k]; }
         else if (i == Lc) { al[i] = 0.0; pl[i] = t; nl[i] = -1; }      // a = [a, 0]
     }
-    if (tid == 0) { bk_i[0] = -1; bk_i[1] = -1; bk_i[2] = -1; bk_i[3] = 0; bk_i[4] = 0; }
+    if (tid == 0) { bk_i[0] = -1; bk_i[1] = -1; bk_i[2] = -1; bk_i[3] = 0; bk_i[4] = 0; bk_i[5] = 0; bk_i[7] = 0; }
     if (has_v) request_v(0);                               // this wave's K is done: its V rows may queue now
     WKV_MARK(1);
 
@@ -301,30 +323,60 @@ void wkv_step_kernel(WkvCache c, const void* __restrict__ q_, const void* __rest
     WKV_MARK(3);
     const double Mx = combine_max(wmax, NW, lane);
 
+    // ---- V phase (all waves): accumulate exp(logit - max) . V
+    S l_run = (S)0;
+    S acc[EPL];
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) acc[e] = (S)0;
+    auto weighted_sum_from = [&](uint32_t (&src)[U][NW32], int r) {
+        const int base = v_base(r), stride = v_stride(r);
+#pragma unroll
+        for (int uu = 0; uu < U; ++uu) {
+            const int i = base + uu * stride;
+            const S p = (i < Ls) ? soft_exp((S)(sl[(i < Ls) ? i : 0] - Mx)) : (S)0;
+            // The row is touched here and not before: left alone, the compiler converts the first V
+            // rows right behind their request, ahead of the first barrier, and every wave then
+            // waits for its V rows before the bookkeeping can even start.
+#pragma unroll
+            for (int w = 0; w < NW32; ++w) asm volatile("" : "+v"(src[uu][w]));
+            float vx[EPL];
+            decode<TT, EPL, NW32>(src[uu], vx);
+            l_run += p;
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) acc[e] += p * (S)vx[e];
+        }
+    };
+    auto weighted_sum = [&](int r) { weighted_sum_from(vw, r); };
+    auto v_first_round = [&]() { weighted_sum(0); };
+
     uint32_t vj_b[EPW] = {}, vr_b[EPW] = {};               // wave 0: the two V rows of the merge (raw)
-    if (wid == 0) {
-        // ---- wave 0: the bookkeeping of Algorithm 1, in fp64, from LDS, while V arrives
+    if (wid < NBK) {
+        // ---- the bookkeeping of Algorithm 1, in fp64, from LDS, while V arrives: wave 0, or waves 0..3
         {   // softmax denominator from the per-wave partial sums; fw[w] rescales wave w's exponentials
+            // (with four bookkeeping waves each computes all of it: same instructions, same bits)
             const double f = (lane < NW) ? exp(wmax[lane] - Mx) : 0.0;
             double den = (lane < NW) ? wsum[lane] * f : 0.0;
             den = readlane_f64(row_allsum(den), 0);
             if (lane < NW) fw[lane] = f / den;
         }
+        WKV_MARK(9);
         Best best = { INFINITY, NONE_POS, -1 };
         int nonfinite = 0;
         // BK entries per lane at a time, in straight-line code: their LDS reads are in flight
         // together and their divisions interleave (one entry at a time, each trip is a chain of
-        // two LDS round trips and a 14-instruction fp64 division that nothing overlaps)
-        constexpr int BK = 4;
+        // two LDS round trips and a 14-instruction fp64 division that nothing overlaps).  Bookkeeping
+        // wave w of NBK takes the 64-entry stretches w, w + NBK, ...
+        constexpr int BK = QUAD ? 2 : 4;
         const int newest_cand = t - c.R, n_sink = c.n_sink;
         auto batches = [&](auto mode_c) {                            // the scoring rule as a constant: no branch per entry
             constexpr int MODE = decltype(mode_c)::value;
-            for (int b0 = 0; b0 < L; b0 += 64 * BK) {
+            for (int b0 = 0; b0 < L; b0 += 64 * BK * NBK) {
                 double e[BK], a[BK], f[BK];
-                int pi[BK];
+                int pi[BK], ie[BK];
 #pragma unroll
                 for (int k = 0; k < BK; ++k) {
-                    const int i = b0 + 64 * k + lane;
+                    const int i = b0 + 64 * (k * NBK + (QUAD ? wid : 0)) + lane;
+                    ie[k] = i;
                     const int ic = (i < L) ? i : L - 1;              // past the end: a duplicate, never stored or ranked
                     e[k] = el[ic]; a[k] = al[ic]; pi[k] = pl[ic];
                     const int ir = ic & (RB - 1);                    // the wave that produced the entry
@@ -333,10 +385,9 @@ void wkv_step_kernel(WkvCache c, const void* __restrict__ q_, const void* __rest
                 double p[BK], ai[BK];
 #pragma unroll
                 for (int k = 0; k < BK; ++k) {
-                    const int i = b0 + 64 * k + lane;
                     p[k] = e[k] * f[k];                              // A_t[i]
                     ai[k] = a[k] + p[k];                             // a = [a, 0] + A_t
-                    if (i < L) al[i] = ai[k];
+                    if (ie[k] < L) al[ie[k]] = ai[k];
                 }
                 if (compress) {
                     double score[BK];
@@ -348,15 +399,15 @@ void wkv_step_kernel(WkvCache c, const void* __restrict__ q_, const void* __rest
                         else sc = p[k];
                         const bool bad = !(sc == sc) | (sc == INFINITY);
                         score[k] = bad ? INFINITY : sc;
-                        nonfinite |= (bad & (b0 + 64 * k + lane < L)) ? 1 : 0;
+                        nonfinite |= (bad & (ie[k] < L)) ? 1 : 0;
                     }
 #pragma unroll
                     for (int k = 0; k < BK; ++k) {                   // selects, no short-circuit: stays one basic block
-                        const bool cand = (b0 + 64 * k + lane < L) & (pi[k] <= newest_cand) & (pi[k] >= n_sink);
+                        const bool cand = (ie[k] < L) & (pi[k] <= newest_cand) & (pi[k] >= n_sink);
                         const bool take = cand & ((score[k] < best.s) | ((score[k] == best.s) & (pi[k] < best.pos)));
                         best.s = take ? score[k] : best.s;
                         best.pos = take ? pi[k] : best.pos;
-                        best.phys = take ? b0 + 64 * k + lane : best.phys;
+                        best.phys = take ? ie[k] : best.phys;
                     }
                 }
             }
@@ -364,76 +415,120 @@ void wkv_step_kernel(WkvCache c, const void* __restrict__ q_, const void* __rest
         if (c.score_mode == 0) batches(std::integral_constant<int, 0>{});
         else if (c.score_mode == 1) batches(std::integral_constant<int, 1>{});
         else batches(std::integral_constant<int, 2>{});
-        if (nonfinite) atomicAdd(&c.status[1], 1);
-        if (compress) {
-            best = wave_argmin(best);
-            int j = best.phys, r = -1;
-            // A candidate always exists (n_sink + R <= m) and is never the newest entry, so it has
-            // a right neighbour.  Should the cache ever be inconsistent, touch nothing and flag it.
-            bool sane = j >= 0 && j < Lc;
-            if (sane) { r = nl[j]; sane = r >= 0 && r <= Lc && r != j; }
-            // The merge needs the V rows of the victim and of its right neighbour: requested here,
-            // used after the second barrier, so that their round trip overlaps the V phase.
-            if (sane && c.merge_mode == 0) {
-                const char* rj = Vc + (size_t)j * ROWB;
-                const char* rr = (r == Lc) ? vu : Vc + (size_t)r * ROWB;
+        WKV_MARK(10);
+        bool insane = false;
+        if (compress) best = wave_argmin(best);
+        WKV_MARK(11);
+        if constexpr (QUAD) {
+        // Each of the four waves requests the two V rows a merge of ITS candidate would need
+        // (the candidate's and its right neighbour's), now, 0.6 us before the winner is known:
+        // the winner's rows are then there when the second barrier opens, and the wave that
+        // holds them forms the merged row.  Requested whatever the case (row 0 when there is
+        // no candidate): these waves have their own V rows in flight, and a request under a
+        // condition would make the wait for those wait for everything.
+        {
+            const int jb = best.phys;
+            const bool okb = jb >= 0 && jb < Lc;
+            const int rb = okb ? nl[jb] : -1;
+            const bool use = okb && rb >= 0 && rb <= Lc && rb != jb;
+            const char* rj = Vc + (size_t)(use ? jb : 0) * ROWB;
+            const char* rr = (use && rb == Lc) ? vu : Vc + (size_t)(use ? rb : 0) * ROWB;
 #pragma unroll
-                for (int e = 0; e < EPW; ++e) {
-                    const int col = (lane + 64 * e < D) ? lane + 64 * e : 0;
-                    vj_b[e] = load_bits<TT>(rj, col);
-                    vr_b[e] = load_bits<TT>(rr, col);
-                }
+            for (int e = 0; e < EPW; ++e) {
+                const int col = (lane + 64 * e < D) ? lane + 64 * e : 0;
+                vj_b[e] = load_bits<TT>(rj, col);
+                vr_b[e] = load_bits<TT>(rr, col);
             }
-            if (lane == 0) {
-                if (sane) {
-                    bk_i[0] = j; bk_i[1] = r; bk_i[2] = best.pos;
-                    bk_d[0] = best.s;
-                    bk_d[1] = al[r] / (double)(t - pl[r] + 1);       // abar of the right neighbour
+        }
+        }
+        if (compress) {
+            if constexpr (QUAD) {
+                // Waves 1..3 hand their candidate to wave 0: record, then a release increment of the
+                // counter (their LDS writes, the score sums of their entries included, are visible
+                // before it).  Wave 0 waits for the three increments; they come unconditionally and
+                // depend on nothing wave 0 does, so the wait ends.
+                double* wb_s = bk_d + 4;                             // [4] candidate scores
+                int* wb_pos = bk_i + 8;                              // [4] their tokens
+                int* wb_phy = bk_i + 12;                             // [4] their entries
+                if (lane == 0) { wb_s[wid] = best.s; wb_pos[wid] = best.pos; wb_phy[wid] = best.phys; }
+                if (wid != 0) {
+                    if (lane == 0) __hip_atomic_fetch_add(&bk_i[5], 1, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
                 } else {
-                    bk_i[3] = 1;
-                    atomicAdd(&c.status[1], 1);
+                    while (__hip_atomic_load(&bk_i[5], __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP) < NBK - 1) {}
+                    Best b = { (lane < NBK) ? wb_s[lane & 3] : INFINITY, (lane < NBK) ? wb_pos[lane & 3] : NONE_POS,
+                               (lane < NBK) ? wb_phy[lane & 3] : -1 };
+                    best_step<0xB1>(b); best_step<0x4E>(b);          // over lanes 0..3
+                    best = { readlane_f64(b.s, 0), __builtin_amdgcn_readlane(b.pos, 0), __builtin_amdgcn_readlane(b.phys, 0) };
                 }
             }
-            if (RANK0) {
-                // the victim's rank in token order, for the log: this wave has nothing else to do
-                // until the second barrier, and the other waves are spared a count, a reduction, an
-                // LDS atomic and a third barrier at the very end of the kernel (cfg3 13.4 -> 13.2 us,
-                // 512 units x 410 slots 21.2 -> 20.9; in large launches it does not pay: 1024 x 1024
-                // 88.2 -> 89.4)
+            if (wid == 0) {
+                int j = best.phys, r = -1;
+                // A candidate always exists (n_sink + R <= m) and is never the newest entry, so it has
+                // a right neighbour.  Should the cache ever be inconsistent, touch nothing and flag it.
+                bool sane = j >= 0 && j < Lc;
+                if (sane) { r = nl[j]; sane = r >= 0 && r <= Lc && r != j; }
+                insane = !sane;
+                if constexpr (!QUAD) {
+                    // The merge needs the V rows of the victim and of its right neighbour: requested here,
+                    // used after the second barrier, so that their round trip overlaps the V phase.
+                    if (sane && c.merge_mode == 0) {
+                        const char* rj = Vc + (size_t)j * ROWB;
+                        const char* rr = (r == Lc) ? vu : Vc + (size_t)r * ROWB;
+#pragma unroll
+                        for (int e = 0; e < EPW; ++e) {
+                            const int col = (lane + 64 * e < D) ? lane + 64 * e : 0;
+                            vj_b[e] = load_bits<TT>(rj, col);
+                            vr_b[e] = load_bits<TT>(rr, col);
+                        }
+                    }
+                }
+                if (lane == 0) {
+                    if (sane) {
+                        bk_i[0] = j; bk_i[1] = r; bk_i[2] = best.pos;
+                        bk_i[6] = (j >> 6) & (NBK - 1);              // the bookkeeping wave that ranked (and fetched for) the victim
+                        bk_d[0] = best.s;
+                        bk_d[1] = al[r] / (double)(t - pl[r] + 1);   // abar of the right neighbour
+                    } else {
+                        bk_i[3] = 1;
+                    }
+                    if constexpr (QUAD)     // the victim is published: wave 1, which ranks it for the log, may go on
+                        __hip_atomic_store(&bk_i[7], 1, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
+                }
+                if (RANK0) {
+                    // the victim's rank in token order, for the log: this wave has nothing else to do
+                    // until the second barrier, and the other waves are spared a count, a reduction, an
+                    // LDS atomic and a third barrier at the very end of the kernel (512 units x 410
+                    // slots 21.2 -> 20.9 us; in large launches it does not pay: 1024 x 1024 88.2 -> 89.4)
+                    int cnt = 0;
+                    for (int i = lane; i < Lc; i += 64) cnt += (pl[i] < best.pos) ? 1 : 0;
+                    cnt = wave_sum(cnt);
+                    if (lane == 0) bk_i[4] = cnt;
+                }
+                WKV_MARK(8);
+            }
+        }
+        if constexpr (QUAD) {
+            // These waves' own V rows, here and not below; the flags for the status word wait until
+            // after: an atomic under a condition would spoil the wait.
+            if (nrounds_v > 0) v_first_round();
+            if (compress && wid == 1) {
+                // The victim's rank in token order, for the log, from the staged token indices: by wave
+                // 1, which has handed in its candidate and used its V rows, ahead of the second barrier
+                // (it waits for wave 0 to publish the victim: that comes unconditionally).
+                while (__hip_atomic_load(&bk_i[7], __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP) == 0) {}
+                const int pv = bk_i[2];
                 int cnt = 0;
-                for (int i = lane; i < Lc; i += 64) cnt += (pl[i] < best.pos) ? 1 : 0;
+                for (int i = lane; i < Lc; i += 64) cnt += (pl[i] < pv) ? 1 : 0;
                 cnt = wave_sum(cnt);
                 if (lane == 0) bk_i[4] = cnt;
             }
         }
-        WKV_MARK(8);
+        if (nonfinite) atomicAdd(&c.status[1], 1);
+        if (insane && lane == 0) atomicAdd(&c.status[1], 1);
     }
 
-    // ---- V phase (all waves): accumulate exp(logit - max) . V
-    S l_run = (S)0;
-    S acc[EPL];
-#pragma unroll
-    for (int e = 0; e < EPL; ++e) acc[e] = (S)0;
-    auto weighted_sum = [&](int r) {
-        const int base = v_base(r), stride = v_stride(r);
-#pragma unroll
-        for (int uu = 0; uu < U; ++uu) {
-            const int i = base + uu * stride;
-            const S p = (i < Ls) ? soft_exp((S)(sl[(i < Ls) ? i : 0] - Mx)) : (S)0;
-            // The row is touched here and not before: left alone, the compiler converts the first V
-            // rows right behind their request, ahead of the first barrier, and every wave then
-            // waits for its V rows before the bookkeeping can even start.
-#pragma unroll
-            for (int w = 0; w < NW32; ++w) asm volatile("" : "+v"(vw[uu][w]));
-            float vx[EPL];
-            decode<TT, EPL, NW32>(vw[uu], vx);
-            l_run += p;
-#pragma unroll
-            for (int e = 0; e < EPL; ++e) acc[e] += p * (S)vx[e];
-        }
-    };
-    if (has_v) {
-        if (nrounds_v > 0) weighted_sum(0);                // the round requested during the K phase
+    // ---- V phase (all waves)
+    auto incoming_value = [&]() {
         if constexpr (SEP) {
             if (own_in_v) {                                // the incoming token, counted by one group only
                 const S p = (g4 == 0) ? soft_exp((S)(sl[Lc] - Mx)) : (S)0;
@@ -444,6 +539,32 @@ void wkv_step_kernel(WkvCache c, const void* __restrict__ q_, const void* __rest
                 for (int e = 0; e < EPL; ++e) acc[e] += p * (S)vx[e];
             }
         }
+    };
+    if constexpr (QUAD) {
+        if (wid >= NBK) {
+            if (nrounds_v > 1) {
+                // A wave with a second round of V rows requests it now, into the K buffer (free since
+                // the K phase), and only then uses the first: a workgroup that got its K rows late --
+                // the kind a launch of a few hundred units ends with -- pays one memory round trip for
+                // its V rows instead of two.  (Both rounds ahead of the barrier stall the wave at the
+                // request: the compute unit's memory pipeline is full of its siblings' V rows by then.)
+                // A path of its own, so that the wait for the first round leaves the second in flight.
+                request_rows(kw, Vc, vu, v_base(1), v_stride(1));
+                weighted_sum_from(vw, 0);
+                incoming_value();
+                weighted_sum_from(kw, 1);
+                for (int r = 2; r < nrounds_v; ++r) { request_v(r); weighted_sum(r); }
+            } else {
+                if (nrounds_v > 0) weighted_sum(0);        // the round requested during the K phase
+                incoming_value();
+            }
+        } else {                                           // the bookkeeping waves have used their first round
+            incoming_value();
+            for (int r = 1; r < nrounds_v; ++r) { request_v(r); weighted_sum(r); }
+        }
+    } else if (has_v) {
+        if (nrounds_v > 0) weighted_sum(0);                // the round requested during the K phase
+        incoming_value();
         for (int r = 1; r < nrounds_v; ++r) { request_v(r); weighted_sum(r); }
     }
     if (has_v) {                                           // a wave without V rows has nothing to add
@@ -477,7 +598,39 @@ void wkv_step_kernel(WkvCache c, const void* __restrict__ q_, const void* __rest
         else store_elem<TT>(out_, (size_t)u * D + col, (float)o);
     }
 
-    if (wid == 0 && sane) {
+    if constexpr (QUAD) {
+        // ---- write-back of the rows.  The merged value by the bookkeeping wave that ranked the victim:
+        // it requested the victim's and the neighbour's rows when it picked its candidate.  The
+        // incoming token's rows by wave 0.
+        const bool merge = compress && sane && c.merge_mode == 0;
+        if (merge && wid == bk_i[6]) {
+            const double sj = bk_d[0], sr = bk_d[1];
+            const double den = sj + sr;
+            const bool zero_den = !(den > 0.0);
+            char* dst = Vc + (size_t)(r == Lc ? dest : r) * ROWB;   // r == Lc: folded straight into the new token
+#pragma unroll
+            for (int e = 0; e < EPW; ++e) {
+                const int col = lane + 64 * e;
+                if (col < D) {
+                    // V[r] <- (abar_j V[j] + abar_r V[r]) / (abar_j + abar_r)     (Algorithm 1, Section IV)
+                    const double vj = (double)bits_elem<TT>(vj_b[e]);
+                    const double vr = (double)bits_elem<TT>(vr_b[e]);
+                    store_elem_f64<TT>(dst, col, zero_den ? 0.5 * vj + 0.5 * vr : (sj * vj + sr * vr) / den);
+                }
+            }
+            if (lane == 0 && zero_den) atomicAdd(&c.status[0], 1);
+        }
+        if (wid == 0 && sane) {
+#pragma unroll
+            for (int e = 0; e < EPW; ++e) {
+                const int col = lane + 64 * e;
+                if (col < D) {
+                    if (!(merge && r == Lc)) store_bits<TT>(Vc + (size_t)dest * ROWB, col, vnew_b[e]);
+                    store_bits<TT>(Kc + (size_t)dest * ROWB, col, knew_b[e]);
+                }
+            }
+        }
+    } else if (wid == 0 && sane) {
         // ---- write-back of the rows: merged value, then the incoming token into its slot
         const bool merge = compress && c.merge_mode == 0;
         const double sj = bk_d[0], sr = bk_d[1];
@@ -518,7 +671,7 @@ void wkv_step_kernel(WkvCache c, const void* __restrict__ q_, const void* __rest
             if (k * NT < L) {                               // uniform: skip rounds no thread needs
                 const int i = tid + k * NT;
                 if (i < Lc) {
-                    if (!RANK0) cnt += (pos_reg[k] < pj) ? 1 : 0;   // the victim's rank in token order, for the log
+                    if (!RANK0 && !QUAD) cnt += (pos_reg[k] < pj) ? 1 : 0;   // the victim's rank in token order, for the log
                     if (i != j) {
                         au[i] = al[i];
                         const int n = nxt_reg[k];
@@ -532,7 +685,7 @@ void wkv_step_kernel(WkvCache c, const void* __restrict__ q_, const void* __rest
                 }
             }
         }
-        if (!RANK0) {
+        if (!RANK0 && !QUAD) {
             if (compress) {
                 cnt = wave_sum(cnt);
                 if (lane == 0 && cnt) atomicAdd(&bk_i[4], cnt);
@@ -540,14 +693,22 @@ void wkv_step_kernel(WkvCache c, const void* __restrict__ q_, const void* __rest
         }
     }
     WKV_MARK(6);
-    if (!RANK0) WKV_LDS_BARRIER();   // barrier 3: the victim's rank is complete (global stores keep flying)
-#undef WKV_LDS_BARRIER
-
-    if (tid == 0) {
-        const size_t row = (size_t)(t % c.log_cap) * c.units + u;
-        c.log_pos[row] = (compress && sane) ? pj : -1;
-        c.log_slot[row] = (compress && sane) ? bk_i[4] : -1;
+    if constexpr (QUAD) {
+        // the log entry, by wave 1, which ranked the victim ahead of the barrier
+        if (tid == 64) {
+            const size_t row = (size_t)(t % c.log_cap) * c.units + u;
+            c.log_pos[row] = (compress && sane) ? pj : -1;
+            c.log_slot[row] = (compress && sane) ? bk_i[4] : -1;
+        }
+    } else {
+        if (!RANK0) WKV_LDS_BARRIER();   // barrier 3: the victim's rank is complete (global stores keep flying)
+        if (tid == 0) {
+            const size_t row = (size_t)(t % c.log_cap) * c.units + u;
+            c.log_pos[row] = (compress && sane) ? pj : -1;
+            c.log_slot[row] = (compress && sane) ? bk_i[4] : -1;
+        }
     }
+#undef WKV_LDS_BARRIER
     WKV_MARK(7);
 }
 
@@ -598,14 +759,14 @@ template <class TT, int D, int U, int MAXT>
 hipError_t prepare_u(size_t lds)
 {
     const void* ks[] = {
-        reinterpret_cast<const void*>(&wkv_step_kernel<TT, D, U, MAXT, false, true, false>),
-        reinterpret_cast<const void*>(&wkv_step_kernel<TT, D, U, MAXT, true, true, false>),
-        reinterpret_cast<const void*>(&wkv_step_kernel<TT, D, U, MAXT, false, (MAXT > 512), false>),
-        reinterpret_cast<const void*>(&wkv_step_kernel<TT, D, U, MAXT, true, (MAXT > 512), false>),
-        reinterpret_cast<const void*>(&wkv_step_kernel<TT, D, U, MAXT, false, true, true>),
-        reinterpret_cast<const void*>(&wkv_step_kernel<TT, D, U, MAXT, true, true, true>),
-        reinterpret_cast<const void*>(&wkv_step_kernel<TT, D, U, MAXT, false, (MAXT > 512), true>),
-        reinterpret_cast<const void*>(&wkv_step_kernel<TT, D, U, MAXT, true, (MAXT > 512), true>),
+        reinterpret_cast<const void*>(&wkv_step_kernel<TT, D, U, MAXT, false, (MAXT <= 512), false>),
+        reinterpret_cast<const void*>(&wkv_step_kernel<TT, D, U, MAXT, true, (MAXT <= 512), false>),
+        reinterpret_cast<const void*>(&wkv_step_kernel<TT, D, U, MAXT, false, false, false>),
+        reinterpret_cast<const void*>(&wkv_step_kernel<TT, D, U, MAXT, true, false, false>),
+        reinterpret_cast<const void*>(&wkv_step_kernel<TT, D, U, MAXT, false, (MAXT <= 512), true>),
+        reinterpret_cast<const void*>(&wkv_step_kernel<TT, D, U, MAXT, true, (MAXT <= 512), true>),
+        reinterpret_cast<const void*>(&wkv_step_kernel<TT, D, U, MAXT, false, false, true>),
+        reinterpret_cast<const void*>(&wkv_step_kernel<TT, D, U, MAXT, true, false, true>),
     };
     for (const void* k : ks) {
         hipError_t e = hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
@@ -651,10 +812,10 @@ hipError_t launch_u(const WkvCache& c, int threads, size_t lds, bool sep, bool s
                     const void* k, const void* v, void* out, int t, hipStream_t stream)
 {
     if constexpr (MAXT <= 512) {
-        if (!dedicated_wave(c, threads, (size_t)D * TT::BYTES, U, sep))
-            return launch_ud<TT, D, U, MAXT, false>(c, threads, lds, sep, stream_loads, q, k, v, out, t, stream);
+        if (dedicated_wave(c, threads, (size_t)D * TT::BYTES, U, sep))
+            return launch_ud<TT, D, U, MAXT, true>(c, threads, lds, sep, stream_loads, q, k, v, out, t, stream);
     }
-    return launch_ud<TT, D, U, MAXT, true>(c, threads, lds, sep, stream_loads, q, k, v, out, t, stream);
+    return launch_ud<TT, D, U, MAXT, false>(c, threads, lds, sep, stream_loads, q, k, v, out, t, stream);
 }
 
 template <class TT, int D, int MAXT>
