@@ -3,8 +3,9 @@
  *
  * WeightedKV (arXiv 2503.01330) keeps a key/value cache of fixed size m during
  * autoregressive decoding.  For every (sequence, head) pair -- a "unit"; the
- * paper drops batch and head dimensions "for simplicity" (Section III-A), so
- * units never interact -- one generated token does the following:
+ * paper writes the method for a single one and leaves batch and head indices
+ * out (Section III-A), so units never interact -- one generated token does the
+ * following:
  *
  *   1. K_t = [K_{t-1}, k_t],  V_t = [V_{t-1}, v_t]                (Section III-A)
  *   2. A_t = softmax(q_t^T K_t / sqrt(d)),  o_t = A_t^T V_t        (Sections III-A, III-B)
@@ -61,10 +62,14 @@ extern "C" {
 
 /* How wkv_step loads the cached K and V rows (wkv_options.streaming).  Every row is read once per
  * step; whether it is still in the 256 MB last-level cache at the next step depends on how much
- * else is streamed in between.  AUTO decides at every step: non-temporal loads when the caches of
- * all live handles on the device together exceed twice that cache (nothing survives until its
- * next use, and loads that allocate cache lines on their way only cost bandwidth) and a row is at
- * most 256 bytes; through the caches otherwise.  Results do not depend on the choice. */
+ * else is streamed in between, which only the caller knows.  CACHED and STREAMING state it:
+ * through the caches, or with non-temporal loads (nothing a step loads survives until its next
+ * use, and loads that allocate cache lines on their way only cost bandwidth; rows of at most
+ * 256 bytes only).  AUTO guesses: it takes the K and V of ALL live handles on the device as what is
+ * streamed between two steps of this handle (a stack of layers stepped in turn) and chooses
+ * STREAMING when that exceeds twice the last-level cache.  The guess is wrong when handles sit idle:
+ * they still count, and a small handle stepped alone next to them loses about a tenth to
+ * non-temporal loads it did not need -- say CACHED there.  Results do not depend on the choice. */
 #define WKV_LOADS_AUTO      0
 #define WKV_LOADS_CACHED    1
 #define WKV_LOADS_STREAMING 2
@@ -88,7 +93,9 @@ typedef struct wkv_options {
     int streaming;               /* optional: WKV_LOADS_*: how wkv_step loads the cached K/V rows  */
     int max_prompt;              /* optional: prompt length (tokens) for which wkv_create_ex already */
                                  /*   reserves wkv_prefill's scratch, so that the call allocates nothing */
-    int reserved[2];             /* must be zero                                                   */
+    int replayable;              /* optional, 0/1: keep the token index in device memory, so that   */
+                                 /*   recorded steps can be replayed from a HIP graph (see wkv_step) */
+    int reserved[1];             /* must be zero                                                   */
 } wkv_options;
 
 /*
@@ -122,9 +129,15 @@ int wkv_create_ex(wkv_handle** h, const wkv_options* opt);
  * slots per unit.  Arguments are checked on the host before anything is
  * launched; on error nothing is enqueued and the cache is unchanged.
  * Steps of one handle must be enqueued in token order on streams that order
- * them (normally one stream).  The token index lives in the handle, on the
- * host, and travels as a kernel argument: a step recorded into a HIP graph
- * would replay that one index, so replaying recorded steps is not supported.
+ * them (normally one stream).
+ * HIP graphs: by default the token index lives in the handle, on the host, and travels as a
+ * kernel argument, so a step recorded into a graph would replay that one index: do not replay
+ * such a recording.  A handle created with wkv_options.replayable = 1 keeps the index in device
+ * memory instead: the kernel reads it when it starts (one dependent scalar load, about a
+ * microsecond per launch) and the last workgroup to finish with it stores index + 1, so a
+ * recorded wkv_step advances with every replay, and recorded and directly enqueued steps may be
+ * mixed.  The caller replays with the buffers it recorded with (a graph fixes q, k_new, v_new and
+ * out).  wkv_state reads the index back from the device, so it counts replays too.
  */
 int wkv_step(wkv_handle* h, const void* q, const void* k_new, const void* v_new,
              void* out, void* stream);

@@ -36,7 +36,7 @@ EXPORTS = ("wkv_create", "wkv_create_ex", "wkv_step", "wkv_prefill", "wkv_prefil
 class wkv_options(C.Structure):
     _fields_ = [(n, C.c_int) for n in ("batch", "heads", "head_dim", "budget", "recent_window",
                                         "dtype", "n_sink", "score_mode", "merge_mode",
-                                        "log_capacity", "threads", "split", "streaming", "max_prompt")] + [("reserved", C.c_int * 2)]
+                                        "log_capacity", "threads", "split", "streaming", "max_prompt", "replayable")] + [("reserved", C.c_int * 1)]
 
 
 class WkvError(RuntimeError):
@@ -88,9 +88,10 @@ def wkv_version() -> int:
 
 
 def make_options(batch, heads, head_dim, budget, recent_window, dtype, n_sink=0, score_mode=0,
-                 merge_mode=0, log_capacity=0, threads=0, split=0, streaming=0, max_prompt=0) -> wkv_options:
+                 merge_mode=0, log_capacity=0, threads=0, split=0, streaming=0, max_prompt=0,
+                 replayable=0) -> wkv_options:
     return wkv_options(batch, heads, head_dim, budget, recent_window, dtype, n_sink, score_mode,
-                       merge_mode, log_capacity, threads, split, streaming, max_prompt)
+                       merge_mode, log_capacity, threads, split, streaming, max_prompt, replayable)
 
 
 def wkv_create(batch, heads, head_dim, budget, recent_window, dtype):

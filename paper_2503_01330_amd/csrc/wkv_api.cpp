@@ -77,6 +77,7 @@ int validate(const wkv_options& o, int* threads, int* split)
         return fail(WKV_EINVAL, "cumulative / last-step scoring are eviction rules: use WKV_MERGE_NONE");
     if (o.log_capacity < 0) return fail(WKV_EINVAL, "log_capacity must be >= 0");
     if (o.streaming < 0 || o.streaming > 2) return fail(WKV_EINVAL, "streaming must be WKV_LOADS_AUTO, _CACHED or _STREAMING");
+    if (o.replayable != 0 && o.replayable != 1) return fail(WKV_EINVAL, "replayable must be 0 or 1");
     if (o.max_prompt < 0 || o.max_prompt > WKV_MAX_PROMPT) return fail(WKV_EINVAL, "max_prompt must be in 0..WKV_MAX_PROMPT");
     if (o.max_prompt > 0 && (o.dtype == WKV_FP32 || o.head_dim > 128))
         return fail(WKV_ESIZE, "max_prompt: wkv_prefill is built for 16-bit caches with head_dim 64 or 128");
@@ -116,8 +117,8 @@ int validate(const wkv_options& o, int* threads, int* split)
         // are equally close (m = 512) 512 threads stay ahead, and beyond they win either way
         // (1400 x 410: 55.3 against 58.6, 2048 x 410: 77.2 against 79.0); below 768 units too
         if (sp == 1 && units >= 768 && units < 1200 && row_bytes == 256 && th == 512 && fits(256) &&
-            wkv_step_padded_rows(o.budget, o.dtype, o.head_dim, 256) * 20 <=
-            wkv_step_padded_rows(o.budget, o.dtype, o.head_dim, 512) * 19)
+            wkv_step_padded_rows(o.budget, o.dtype, o.head_dim, 256, units) * 20 <=
+            wkv_step_padded_rows(o.budget, o.dtype, o.head_dim, 512, units) * 19)
             th = 256;
         while (th < 1024 && !fits(th)) th *= 2;
     }
@@ -148,7 +149,8 @@ Sizes sizes(const wkv_options& o, int split)
     s.cnt = split > 1 ? units * sizeof(uint32_t) : 0;
     // wkv_prefill's scratch, when reserved at creation
     const size_t pf = 2 * units * (size_t)(o.max_prompt > 0 ? o.max_prompt : 0) * sizeof(double);
-    s.total = 2 * s.kv + s.a + 2 * s.i32 + 2 * s.log + s.status + s.lg + s.po + 3 * s.ps + s.cnt + pf;
+    s.total = 2 * s.kv + s.a + 2 * s.i32 + 2 * s.log + s.status + s.lg + s.po + 3 * s.ps + s.cnt + pf +
+              (o.replayable ? 16 : 0);
     return s;
 }
 
@@ -342,6 +344,23 @@ int wkv_create_ex(wkv_handle** hp, const wkv_options* opt)
             return rc;
         }
     }
+    if (opt->replayable) {
+        // token index and ticket counter on the device (both start at zero)
+        void* clk = nullptr;
+        e = hipMalloc(&clk, 16);
+        if (e == hipSuccess) e = hipMemset(clk, 0, 16);
+        if (e != hipSuccess) {
+            rc = fail(e == hipErrorOutOfMemory ? WKV_ENOMEM : WKV_EHIP, "device allocation of the step counter: %s", hipGetErrorString(e));
+            (void)hipGetLastError();
+            if (clk) (void)hipFree(clk);
+            for (auto& b2 : bufs) if (*b2.p) (void)hipFree(*b2.p);
+            if (h->pf_scratch) (void)hipFree(h->pf_scratch);
+            delete h;
+            return rc;
+        }
+        c.tdev = static_cast<int64_t*>(clk);
+        c.tick = reinterpret_cast<uint32_t*>(static_cast<char*>(clk) + 8);
+    }
     count_live(h->device, 2 * (long long)s.kv);
     *hp = h;
     return WKV_OK;
@@ -387,6 +406,10 @@ int wkv_prefill(wkv_handle* h, const void* q, const void* k, const void* v, void
     const hipError_t e = wkv_launch_prefill(h->c, h->opt.dtype, h->opt.head_dim, q, k, v, out, lse, a, n_tokens,
                                             (hipStream_t)stream);
     if (e != hipSuccess) return fail(WKV_EHIP, "kernel launch: %s", hipGetErrorString(e));
+    if (h->c.tdev) {
+        const hipError_t e3 = wkv_launch_set_clock(h->c, n_tokens, (hipStream_t)stream);
+        if (e3 != hipSuccess) return fail(WKV_EHIP, "kernel launch: %s", hipGetErrorString(e3));
+    }
     h->t = n_tokens;
     h->log_from = n_tokens;
     return WKV_OK;
@@ -408,6 +431,10 @@ int wkv_prefill_noalloc(wkv_handle* h, const void* q, const void* k, const void*
     double* a = lse + (size_t)h->c.units * (size_t)n_tokens;
     e = wkv_launch_prefill(h->c, h->opt.dtype, h->opt.head_dim, q, k, v, out, lse, a, n_tokens, (hipStream_t)stream);
     if (e != hipSuccess) return fail(WKV_EHIP, "kernel launch: %s", hipGetErrorString(e));
+    if (h->c.tdev) {
+        const hipError_t e3 = wkv_launch_set_clock(h->c, n_tokens, (hipStream_t)stream);
+        if (e3 != hipSuccess) return fail(WKV_EHIP, "kernel launch: %s", hipGetErrorString(e3));
+    }
     h->t = n_tokens;
     h->log_from = n_tokens;
     return WKV_OK;
@@ -417,6 +444,16 @@ static int state_impl(wkv_handle* h, int what, void* dst, size_t bytes)
 {
     const WkvCache& c = h->c;
     const size_t units = c.units, cap = c.m;
+    if (c.tdev) {
+        // replayable handle: the device counts the steps (graph replays advance it without the host)
+        int rc0 = on_device(h);
+        if (rc0 != WKV_OK) return rc0;
+        hipError_t e0 = hipDeviceSynchronize();
+        int64_t td = 0;
+        if (e0 == hipSuccess) e0 = hipMemcpy(&td, c.tdev, sizeof td, hipMemcpyDeviceToHost);
+        if (e0 != hipSuccess) return fail(WKV_EHIP, "reading the step counter: %s", hipGetErrorString(e0));
+        h->t = td;
+    }
     const int64_t T = h->t;
     const size_t len = (size_t)std::min<int64_t>(T, c.m);
     if (what == WKV_STEP) {
@@ -573,6 +610,10 @@ static int load_impl(wkv_handle* h, int64_t tokens, int len, const void* K, cons
     if (e == hipSuccess) e = hipMemcpy(c.nxt, hn.data(), hn.size() * 4, hipMemcpyHostToDevice);
     if (e == hipSuccess) e = hipMemset(c.log_pos, 0xFF, (size_t)c.log_cap * units * 4);
     if (e == hipSuccess) e = hipMemset(c.log_slot, 0xFF, (size_t)c.log_cap * units * 4);
+    if (e == hipSuccess && c.tdev) {
+        e = wkv_launch_set_clock(c, tokens, nullptr);
+        if (e == hipSuccess) e = hipDeviceSynchronize();
+    }
     if (e != hipSuccess) return fail(WKV_EHIP, "uploading the state: %s (the cache may be partly overwritten)", hipGetErrorString(e));
     h->t = tokens;
     h->log_from = tokens;
@@ -615,6 +656,7 @@ int wkv_destroy(wkv_handle* h)
                      h->sp.lg, h->sp.po, h->sp.pm, h->sp.pl, h->sp.pe, h->sp.cnt };
     for (void* b : bufs) if (b) (void)hipFree(b);
     if (h->pf_scratch) (void)hipFree(h->pf_scratch);
+    if (c.tdev) (void)hipFree(c.tdev);
     count_live(h->device, -2 * (long long)sizes(h->opt, h->sp.S).kv);
     if (moved) (void)hipSetDevice(cur);
     delete h;

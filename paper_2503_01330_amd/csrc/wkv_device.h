@@ -250,6 +250,22 @@ template <class X> __device__ __forceinline__ X load_agent(X* p) {
     return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
+// The token index of a step.  Normally a kernel argument from the host.  A handle created
+// "replayable" keeps it in device memory instead, so that a step recorded into a HIP graph advances
+// with every replay.  Every workgroup reads it at its start; when a workgroup is done with it, one
+// of its threads draws a ticket, and the thread that draws the last ticket of the launch -- every
+// workgroup has read the index by then -- stores index + 1 for the next launch and clears the
+// tickets.  (Visibility to the next launch comes with the kernel boundary.)
+template <class Cache> __device__ __forceinline__ int step_index(const Cache& c, int t_arg) {
+    return c.tdev ? (int)*c.tdev : t_arg;
+}
+template <class Cache> __device__ __forceinline__ void step_done(const Cache& c, int t, unsigned workgroups) {
+    if (c.tdev) {
+        const unsigned ticket = atomicAdd(c.tick, 1u);
+        if (ticket == workgroups - 1) { *c.tick = 0u; *c.tdev = (int64_t)t + 1; }
+    }
+}
+
 constexpr int MAXPT = 4;       // entries whose a/pos one thread fetches ahead of the streaming loop
 constexpr int NONE_POS = 0x7FFFFFFF;
 

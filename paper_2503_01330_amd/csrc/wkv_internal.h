@@ -27,8 +27,13 @@ struct WkvCache {
     int32_t* log_pos;    // [log_cap][units] evicted token index per step (ring), -1 = none
     int32_t* log_slot;   // [log_cap][units] its rank in token order
     int32_t* status;     // [2] {zero-denominator merges, non-finite scores / inconsistencies}
+    int64_t* tdev;       // null, or (replayable handles) [1] the token index of the next step, kept on the device
+    uint32_t* tick;      // with tdev: [1] workgroups of the running step that have finished with the index
     int units, m, R, n_sink, score_mode, merge_mode, log_cap;
 };
+
+// Sets a replayable handle's device-side token index (after a prefill or a load): one tiny kernel.
+hipError_t wkv_launch_set_clock(const WkvCache& c, int64_t tokens, hipStream_t stream);
 
 // Launches one decode step for every unit.  t = 0-based index of the incoming
 // token.  threads in {256,512,1024}, with m + 1 <= wkv_step_max_entries(threads).
@@ -37,9 +42,10 @@ hipError_t wkv_launch_step(const WkvCache& c, int dtype, int head_dim, int threa
                            const void* q, const void* k_new, const void* v_new, void* out,
                            int64_t t, hipStream_t stream);
 
-// Row requests per matrix, group and step that wkv_launch_step issues for a budget of m slots,
-// padding of the last chunk included (the chunk depth it would choose is taken into account).
-int wkv_step_padded_rows(int m, int dtype, int head_dim, int threads);
+// Row requests per matrix, group and step that wkv_launch_step issues for a budget of m slots in a
+// launch of `units` units, padding of the last chunk included (the chunk depth it would choose for
+// that launch is taken into account).
+int wkv_step_padded_rows(int m, int dtype, int head_dim, int threads, int units);
 
 // Bytes of dynamic LDS wkv_launch_step needs for this shape.
 size_t wkv_step_lds_bytes(int m, int dtype, int head_dim, int threads);

@@ -34,9 +34,10 @@ namespace {
 template <class TT, int D, int U, int MAXT, bool STREAM>
 __global__ __launch_bounds__(MAXT)
 void wkv_split_kernel(WkvCache c, WkvSplit sp, const void* __restrict__ q_, const void* __restrict__ k_,
-                      const void* __restrict__ v_, void* __restrict__ out_, int t)
+                      const void* __restrict__ v_, void* __restrict__ out_, int t_arg)
 {
     using S = typename TT::soft_t;
+    const int t = step_index(c, t_arg);          // from the host, or (replayable handles) from device memory
     constexpr int EPL  = D / ROW_LANES;
     constexpr int NW32 = EPL * TT::BYTES / 4;
     constexpr int ROWB = D * TT::BYTES;
@@ -228,7 +229,10 @@ void wkv_split_kernel(WkvCache c, WkvSplit sp, const void* __restrict__ q_, cons
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
     __builtin_amdgcn_s_waitcnt(0);                         // vmcnt(0) expcnt(0) lgkmcnt(0)
     __syncthreads();
-    if (tid == 0) misc[0] = (int)atomicAdd(&sp.cnt[u], 1u);
+    if (tid == 0) {
+        misc[0] = (int)atomicAdd(&sp.cnt[u], 1u);
+        step_done(c, t, gridDim.x);                        // every wave of this workgroup has read the index long ago
+    }
     __syncthreads();
     if (misc[0] != NS - 1) return;                         // uniform: somebody else finishes this unit
 

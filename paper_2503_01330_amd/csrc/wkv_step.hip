@@ -83,9 +83,10 @@ namespace {
 template <class TT, int D, int U, int MAXT, bool SEP, bool DED, bool STREAM>
 __global__ __launch_bounds__(MAXT, 4)
 void wkv_step_kernel(WkvCache c, const void* __restrict__ q_, const void* __restrict__ k_,
-                     const void* __restrict__ v_, void* __restrict__ out_, int t)
+                     const void* __restrict__ v_, void* __restrict__ out_, int t_arg)
 {
     using S = typename TT::soft_t;
+    const int t = step_index(c, t_arg);          // from the host, or (replayable handles) from device memory
     // QUAD (the 1024-thread workgroups, one per compute unit): Algorithm 1's bookkeeping is shared by
     // four waves, one on each SIMD of the compute unit, which stream V like everybody else.  A wave
     // issues one instruction every four cycles at best, whatever the instruction, and the
@@ -699,6 +700,7 @@ void wkv_step_kernel(WkvCache c, const void* __restrict__ q_, const void* __rest
             const size_t row = (size_t)(t % c.log_cap) * c.units + u;
             c.log_pos[row] = (compress && sane) ? pj : -1;
             c.log_slot[row] = (compress && sane) ? bk_i[4] : -1;
+            step_done(c, t, gridDim.x);
         }
     } else {
         if (!RANK0) WKV_LDS_BARRIER();   // barrier 3: the victim's rank is complete (global stores keep flying)
@@ -706,6 +708,7 @@ void wkv_step_kernel(WkvCache c, const void* __restrict__ q_, const void* __rest
             const size_t row = (size_t)(t % c.log_cap) * c.units + u;
             c.log_pos[row] = (compress && sane) ? pj : -1;
             c.log_slot[row] = (compress && sane) ? bk_i[4] : -1;
+            step_done(c, t, gridDim.x);
         }
     }
 #undef WKV_LDS_BARRIER
@@ -842,26 +845,36 @@ size_t wkv_step_lds_bytes(int m, int dtype, int head_dim, int threads)
 int wkv_step_max_entries(int threads) { return MAXPT * threads; }
 
 namespace {
-template <class TT, int D, int MAXT> int padded_rows(int m, int threads)
+template <class TT, int D, int MAXT> int padded_rows(int m, int threads, int units)
 {
     constexpr int U = unroll<TT, D, MAXT>();
     const int ng = threads / ROW_LANES;
     if constexpr (has_half_chunk<TT, D, MAXT>()) {
-        if (shallow_rounds(m, ng, U)) return round_slots(m, ng * (U / 2));
+        if (shallow_rounds(m, ng, U, units)) return round_slots(m, ng * (U / 2));
     }
     return round_slots(m, ng * U);
 }
 }  // namespace
 
-int wkv_step_padded_rows(int m, int dtype, int head_dim, int threads)
+int wkv_step_padded_rows(int m, int dtype, int head_dim, int threads, int units)
 {
 #define WKV_CASE(DT, TT, DD) \
-    if (dtype == DT && head_dim == DD) return threads > 512 ? padded_rows<TT, DD, 1024>(m, threads) : padded_rows<TT, DD, 512>(m, threads);
+    if (dtype == DT && head_dim == DD) return threads > 512 ? padded_rows<TT, DD, 1024>(m, threads, units) : padded_rows<TT, DD, 512>(m, threads, units);
     WKV_CASE(0, TF32, 64)  WKV_CASE(0, TF32, 128)
     WKV_CASE(1, TF16, 64)  WKV_CASE(1, TF16, 128)  WKV_CASE(1, TF16, 256)
     WKV_CASE(2, TBF16, 64) WKV_CASE(2, TBF16, 128) WKV_CASE(2, TBF16, 256)
 #undef WKV_CASE
     return 0;
+}
+
+namespace {
+__global__ void wkv_set_clock_kernel(WkvCache c, long long tokens) { *c.tdev = tokens; *c.tick = 0u; }
+}  // namespace
+
+hipError_t wkv_launch_set_clock(const WkvCache& c, int64_t tokens, hipStream_t stream)
+{
+    hipLaunchKernelGGL(wkv_set_clock_kernel, dim3(1), dim3(1), 0, stream, c, (long long)tokens);
+    return hipGetLastError();
 }
 
 hipError_t wkv_step_prepare(int dtype, int head_dim, size_t lds)
