@@ -45,6 +45,8 @@ def parse():
     ap.add_argument("--workload", default="cfg3", choices=["cfg2", "cfg3", "cfg4", "cfg5"])
     ap.add_argument("--layers", type=int, default=0, help="override the number of stacked layers")
     ap.add_argument("--threads", type=int, default=0, help="workgroup size override (256/512/1024)")
+    ap.add_argument("--loads", choices=("auto", "cached", "streaming"), default="auto",
+                    help="how cached rows are loaded (wkv_options.streaming); auto = the library decides")
     ap.add_argument("--split", type=int, default=0, help="workgroups per unit override (1/2/4/8/16; 0 = library's choice)")
     ap.add_argument("--prefill-tokens", type=int, default=4096,
                     help="prompt length of the bulk-prefill leg reported under 'prefill' (0 = skip it)")
@@ -123,7 +125,8 @@ def main():
             bufs.append((tq, tk, tv, out))
             ptrs.append(tuple(x.data_ptr() for x in (tq, tk, tv, out)))
             caches.append(wkv.Cache(cfg.batch, cfg.heads, cfg.head_dim, cfg.budget, cfg.recent, code,
-                                    threads=threads, split=split))
+                                    threads=threads, split=split,
+                                    streaming={"auto": 0, "cached": 1, "streaming": 2}[args.loads]))
         gen_s = time.perf_counter() - t0
         stride = cfg.units * cfg.head_dim * eb
         stream = torch.cuda.current_stream().cuda_stream
@@ -234,6 +237,7 @@ def main():
         "config": {"workload": describe(m, args.workload),
                    "units_per_launch": cfg.units, "launches_per_step": layers,
                    "threads_per_workgroup": args.threads or "auto",
+                   "row_loads": args.loads,
                    "workgroups_per_unit": args.split or "auto",
                    "repetitions": {"timed_regions": REPS, "steps_each": K, "reported": "median",
                                    "ms_per_step_min_max": [round(min(m["walls"]) * 1e3 / K, 4),

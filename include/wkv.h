@@ -67,7 +67,7 @@ extern "C" {
  * use, and loads that allocate cache lines on their way only cost bandwidth; rows of at most
  * 256 bytes only).  AUTO guesses: it takes the K and V of ALL live handles on the device as what is
  * streamed between two steps of this handle (a stack of layers stepped in turn) and chooses
- * STREAMING when that exceeds twice the last-level cache.  The guess is wrong when handles sit idle:
+ * STREAMING when that exceeds the last-level cache by an eighth or more.  The guess is wrong when handles sit idle:
  * they still count, and a small handle stepped alone next to them loses about a tenth to
  * non-temporal loads it did not need -- say CACHED there.  Results do not depend on the choice. */
 #define WKV_LOADS_AUTO      0

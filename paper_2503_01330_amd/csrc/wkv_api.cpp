@@ -45,15 +45,17 @@ void count_live(int device, long long bytes)
 
 // Non-temporal row loads: asked for, or (AUTO) nothing a step loads can still be cached at the next
 // step.  Measured on an MI355X: 2048 units x 512 slots x 256 B, one handle (538 MB): 102 -> 91 us
-// per step; 32 handles of 54 MB stepped in turn: 15.1 -> 14.8; one handle of 273 MB, about the size
-// of the cache: 44.5 -> 46.5, and anything smaller loses more; rows of 512 B lose 11 % at any size
-// (a lane's two 16-byte loads of a row share their 64-byte segments, which then travel twice).
+// per step; handles of 54 MB (256 units x 410 slots) stepped in turn, us per step cached / non-temporal:
+// 4 handles 12.2 / -, 5 (270 MB) 12.32 / 12.43, 6 (324 MB) 12.86 / 12.47, 8 13.75 / 12.54, 12 13.63 / 12.61;
+// one handle of 273 MB: 44.5 / 46.5.  The two cross a little above the size of the cache.  Rows of
+// 512 B lose 11 % at any size (a lane's two 16-byte loads of a row share their 64-byte segments,
+// which then travel twice).
 bool stream_loads(const wkv_options& o, int device)
 {
     if (o.streaming == WKV_LOADS_STREAMING) return true;
     if (o.streaming == WKV_LOADS_CACHED) return false;
     const long long live = (device >= 0 && device < MAX_DEVICES) ? g_live_kv[device].load() : 0;
-    return o.head_dim * dtype_bytes(o.dtype) <= 256 && live >= 2 * LAST_LEVEL_CACHE;
+    return o.head_dim * dtype_bytes(o.dtype) <= 256 && live >= LAST_LEVEL_CACHE + LAST_LEVEL_CACHE / 8;
 }
 
 // Returns 0 and fills *threads and *split, or a negative code with the reason in g_err.
