@@ -18,8 +18,10 @@
 //     (fp64 for an fp32 cache);
 //   * the score bookkeeping of Algorithm 1 (softmax denominator, a += A_t,
 //     abar = a/n, arg-min, right neighbour, merge weights) is done by wave 0
-//     from the staged logit row while V is in flight, so the dependent chain of
-//     the compression hides behind the second half of the memory traffic;
+//     -- in the 1024-thread workgroups by waves 0..3, one on each SIMD of the
+//     compute unit -- from the staged logit row while V is in flight, so the
+//     dependent chain of the compression hides behind the second half of the
+//     memory traffic;
 //   * the bookkeeping is fp64 throughout.  That costs one extra convert per K
 //     element on a memory-bound kernel and makes the eviction decision reproduce
 //     an fp64 reference exactly (differences ~1e-15 relative in abar) instead of
@@ -35,8 +37,8 @@
 // indices, links) is requested before the streaming loop starts, wave-level
 // reductions use DPP row operations plus v_readlane instead of LDS permutes,
 // per-wave results are combined by one DPP row reduction per wave, and the two
-// V rows of the merge are requested by wave 0 the moment it knows which they are,
-// well ahead of the barrier after which it needs them.
+// V rows of the merge are requested the moment a bookkeeping wave knows its
+// candidate, well ahead of the barrier after which they are needed.
 #include "wkv_internal.h"
 #include <type_traits>
 
@@ -56,21 +58,22 @@ namespace {
 // Shape of the kernel (one workgroup per unit):
 //   1. small loads (query, score sums, token indices, links, incoming row), then the K
 //      rows of the first round, are requested before anything is waited for.  Every wave
-//      issues the same loads in straight-line code: s_waitcnt counts are derived per
-//      control-flow path by the compiler, and a conditional request would make every later
-//      wait conservative;
+//      issues its row loads in straight-line code: s_waitcnt counts are derived per
+//      control-flow path by the compiler, and a request under a condition between a load and
+//      its use would make every later wait conservative (conditions ahead of the first row
+//      request are harmless: which small loads a wave issues is decided there);
 //   2. K phase: logits in fp64, to LDS.  A wave requests its first round of V rows as soon
 //      as it has used its last K row, so the memory system is never idle but mostly serves
 //      K before V;
-//   3. barrier 1 (LDS traffic only; the V requests stay in flight).  Then wave 0 does the
-//      bookkeeping of Algorithm 1 in fp64 (softmax denominator, a += A_t, abar = a/n,
-//      arg-min, right neighbour) from LDS while V arrives and the waves accumulate
-//      exp(logit - max) . V;
-//   4. barrier 2: victim and neighbour are known.  Wave 0, which requested the two V rows of
-//      the merge as soon as it knew them, writes the merged row and the incoming token's rows;
-//      every thread writes back the score sum and link of the entry it owns; the last waves
-//      write o_t; barrier 3; the log entry (the 1024-thread workgroups need no third barrier:
-//      their wave 0 has ranked the victim for the log while it waited for the second).
+//   3. barrier 1 (LDS traffic only; the V requests stay in flight).  Then the bookkeeping
+//      of Algorithm 1 in fp64 (softmax denominator, a += A_t, abar = a/n, arg-min, right
+//      neighbour) from LDS, by wave 0 or by waves 0..3 (QUAD below), while V arrives and the
+//      waves accumulate exp(logit - max) . V;
+//   4. barrier 2: victim and neighbour are known.  The wave that requested the two V rows of
+//      the merge writes the merged row, wave 0 the incoming token's rows; every thread writes
+//      back the score sum and link of the entry it owns; the last waves write o_t; barrier 3;
+//      the log entry (the 1024-thread workgroups need no third barrier: a bookkeeping wave has
+//      ranked the victim for the log while it waited for the second).
 //
 // SEP: the incoming token is attended outside the rounds (by the wave whose block would have
 // held it).  Chosen by the host when the budget is a multiple of the block, where entry m would
@@ -736,7 +739,8 @@ inline bool shallow_rounds(int m, int ng, int rows_per_group, int units = 1 << 3
     return round_slots(m, ng * (rows_per_group / 2)) * 10 <= round_slots(m, ng * rows_per_group) * 9;
 }
 
-// Wave 0 is kept free of V rows (DED at the kernel) in the 1024-thread workgroups always.  In
+// Wave 0 is kept free of V rows (DED at the kernel) in workgroups of up to 512 threads only (the
+// 1024-thread workgroups share the bookkeeping among four waves instead, which all stream V).  In
 // those of 512 threads when a matrix takes three rounds or more (one wave fewer among eight then
 // adds little to each of the others, and wave 0's bookkeeping stops being the longest job of the
 // workgroup); with fewer rounds, and in workgroups of 256 threads, only when the launch is not
@@ -749,7 +753,6 @@ inline bool shallow_rounds(int m, int ng, int rows_per_group, int units = 1 << 3
 // one round: 4096 x 256 99.1 / 97.8; 256 threads: 768 x 410 29.9 / 29.3.
 inline bool dedicated_wave(const WkvCache& c, int threads, size_t row_bytes, int rows_per_group, bool sep)
 {
-    if (threads > 512) return true;
     const int ls = sep ? c.m : c.m + 1, ng = threads / ROW_LANES;
     const int chunk = ng * rows_per_group, chunk_v = (ng - 4) * rows_per_group;
     const int rounds = (ls + chunk - 1) / chunk, rounds_v = (ls + chunk_v - 1) / chunk_v;

@@ -84,3 +84,18 @@ def test_workgroups_per_unit_are_chosen_by_shape():
     assert ws(8, 32, 410) == ws(8, 32, 410, split=1)
     assert ws(1, 32, 256) == ws(1, 32, 256, split=1)
     assert ws(4, 32, 2048) == ws(4, 32, 2048, split=1) + scratch(128, 2048, 2)
+
+
+def test_launch_shape_follows_the_unit_count():
+    """Host-only: the grid wkv_step would launch.  256 units: one workgroup of 1024 threads each;
+    one sequence of a 32-head model with 819 slots: 4 slices per unit in 512-thread workgroups;
+    2048 units: 512 threads, one workgroup per unit; explicit requests win; bad options are refused."""
+    def shape(batch, heads, m, **kw):
+        return wkv.wkv_launch_shape(wkv.make_options(batch, heads, 128, m, 32, wkv.WKV_FP16, **kw))
+    assert shape(8, 32, 410) == (256, 1024)
+    assert shape(1, 32, 819) == (128, 512)
+    assert shape(4, 32, 2048) == (256, 1024)
+    assert shape(64, 32, 512) == (2048, 512)
+    assert shape(8, 32, 410, threads=512, split=2) == (512, 512)
+    with pytest.raises(wkv.WkvError):
+        shape(8, 32, 410, threads=300)
