@@ -162,6 +162,20 @@ __device__ __forceinline__ double4_t logits_tile(const uint32_t (&kfrag)[D / 8],
     return (s0 + s1) * scale;
 }
 
+// The same tile with both operands already in fp64: for a loop in which one operand never changes
+// (its conversions are then paid once, not once per tile).
+template <int D>
+__device__ __forceinline__ double4_t logits_tile(const double (&kd)[D / 4], const double (&qd)[D / 4]) {
+    double4_t s0 = {0.0, 0.0, 0.0, 0.0}, s1 = {0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+    for (int kk = 0; kk < D / 4; kk += 2) {
+        s0 = __builtin_amdgcn_mfma_f64_16x16x4f64(kd[kk], qd[kk], s0, 0, 0, 0);
+        s1 = __builtin_amdgcn_mfma_f64_16x16x4f64(kd[kk + 1], qd[kk + 1], s1, 0, 0, 0);
+    }
+    const double scale = 1.0 / sqrt((double)D);
+    return (s0 + s1) * scale;
+}
+
 // ------------------------------------------------------------------ 1. rows
 // q, k, v, out: [P][units][D] (token-major, as a decode step sees them one token at a time).
 // lse: [units][P].  One workgroup = 4 waves = 4 consecutive query tiles of one unit.
@@ -305,8 +319,14 @@ void wkv_prefill_scores(const void* __restrict__ q_, const void* __restrict__ k_
     const char* qb = reinterpret_cast<const char*>(q_) + (size_t)u * ROWB;
     const char* kb = reinterpret_cast<const char*>(k_) + (size_t)u * ROWB;
 
-    uint32_t kfrag[CH / 2];
-    load_words<CH / 2>(kb + (size_t)min(kt * TILE + x, P - 1) * tok + g * CH * TT::BYTES, kfrag);
+    // the wave's key fragment never changes: converted to fp64 once (64 registers), not once per query tile
+    double kd[CH];
+    {
+        uint32_t kfrag[CH / 2];
+        load_words<CH / 2>(kb + (size_t)min(kt * TILE + x, P - 1) * tok + g * CH * TT::BYTES, kfrag);
+#pragma unroll
+        for (int e = 0; e < CH; ++e) kd[e] = (double)frag_elem<TT>(kfrag, e);
+    }
     double acc[4] = {0.0, 0.0, 0.0, 0.0};
     uint32_t wnext[CH / 2];
     double lnext;
@@ -327,7 +347,7 @@ void wkv_prefill_scores(const void* __restrict__ q_, const void* __restrict__ k_
 #pragma unroll
         for (int e = 0; e < CH; ++e) qd[e] = (double)frag_elem<TT>(wnext, e);
         request(min(kt + 1, ntiles - 1));
-        s_cur = logits_tile<TT, D>(kfrag, qd);
+        s_cur = logits_tile<D>(kd, qd);
     }
     for (int qt = kt; qt < ntiles; ++qt) {
         const int tq = qt * TILE + x;
@@ -337,7 +357,7 @@ void wkv_prefill_scores(const void* __restrict__ q_, const void* __restrict__ k_
         const double l_next = lnext;
         request(min(qt + 2, ntiles - 1));
         __builtin_amdgcn_sched_barrier(0);                                 // the requests are issued here, not later
-        double4_t s_next = logits_tile<TT, D>(kfrag, qd);                 // tile qt + 1 (a repeat on the last round)
+        double4_t s_next = logits_tile<D>(kd, qd);                 // tile qt + 1 (a repeat on the last round)
         // The fragment just requested may be touched only once this chain has been issued: without
         // these opaque uses the compiler converts it right behind its request, i.e. every round
         // waits for the loads it has just issued.
