@@ -216,26 +216,29 @@ void wkv_prefill_rows(const void* __restrict__ q_, const void* __restrict__ k_, 
     for (int e = 0; e < NE; ++e) o[e] = float4_t{0.f, 0.f, 0.f, 0.f};
 
     // K fragment of a key tile: key 16 kt + x, the same quarter of the row as the query fragment.
-    // V fragments: keys 16 kt + g + 4r, columns NE*x .. NE*x+NE-1.  The fragments of the next tile are
-    // requested before the current tile is worked on.
-    uint32_t knext[CH / 2], vnext[4][NE / 2];
-    auto request = [&](int kt) {
-        load_words<CH / 2>(kb + (size_t)min(kt * TILE + x, P - 1) * tok + g * CH * TT::BYTES, knext);
+    // V fragments: keys 16 kt + g + 4r, columns NE*x .. NE*x+NE-1.  Two sets of fragment registers
+    // take turns: the next tile is requested into one set before the current tile is worked on
+    // from the other, so no fragment is ever copied.  A lane's byte offsets inside a tile never
+    // change; the tile's base address is uniform (scalar arithmetic), so a request costs one vector
+    // add per load.  Only a tile that reaches past the end of the prompt clamps its rows.
+    const size_t koff = (size_t)x * tok + g * CH * TT::BYTES;
+    size_t voff[4];
 #pragma unroll
-        for (int r = 0; r < 4; ++r)
-            load_words<NE / 2>(vb + (size_t)min(kt * TILE + g + 4 * r, P - 1) * tok + x * NE * TT::BYTES, vnext[r]);
+    for (int r = 0; r < 4; ++r) voff[r] = (size_t)(g + 4 * r) * tok + x * NE * TT::BYTES;
+    auto request = [&](int kt, uint32_t (&kf)[CH / 2], uint32_t (&vf)[4][NE / 2]) __attribute__((always_inline)) {
+        if (kt * TILE + TILE <= P) {                          // uniform
+            const size_t base = (size_t)kt * TILE * tok;
+            load_words<CH / 2>(kb + base + koff, kf);
+#pragma unroll
+            for (int r = 0; r < 4; ++r) load_words<NE / 2>(vb + base + voff[r], vf[r]);
+        } else {
+            load_words<CH / 2>(kb + (size_t)min(kt * TILE + x, P - 1) * tok + g * CH * TT::BYTES, kf);
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+                load_words<NE / 2>(vb + (size_t)min(kt * TILE + g + 4 * r, P - 1) * tok + x * NE * TT::BYTES, vf[r]);
+        }
     };
-    request(0);
-    for (int kt = 0; kt <= qt; ++kt) {
-        uint32_t kfrag[CH / 2], vfrag[4][NE / 2];
-#pragma unroll
-        for (int w = 0; w < CH / 2; ++w) kfrag[w] = knext[w];
-#pragma unroll
-        for (int r = 0; r < 4; ++r)
-#pragma unroll
-            for (int w = 0; w < NE / 2; ++w) vfrag[r][w] = vnext[r][w];
-        request(min(kt + 1, qt));                             // the last request repeats a tile, unused
-
+    auto tile = [&](int kt, const uint32_t (&kfrag)[CH / 2], const uint32_t (&vfrag)[4][NE / 2]) __attribute__((always_inline)) {
         double4_t s = logits_tile<TT, D>(kfrag, qd);
         if (kt == qt) {                       // the diagonal tile: key g + 4r may be attended by query x only if <= x
 #pragma unroll
@@ -280,6 +283,15 @@ void wkv_prefill_rows(const void* __restrict__ q_, const void* __restrict__ k_, 
 #pragma unroll
             for (int w = 0; w < weight_parts<TT>(); ++w) o[e] = mfma16<TT>(pa[w], vb, o[e]);
         }
+    };
+    uint32_t kf0[CH / 2], vf0[4][NE / 2], kf1[CH / 2], vf1[4][NE / 2];
+    request(0, kf0, vf0);
+    for (int kt = 0; kt <= qt; kt += 2) {
+        request(min(kt + 1, qt), kf1, vf1);                   // past the last tile: a repeat, unused
+        tile(kt, kf0, vf0);
+        if (kt + 1 > qt) break;
+        request(min(kt + 2, qt), kf0, vf0);
+        tile(kt + 1, kf1, vf1);
     }
 
     // o_t = O / l, log-sum-exp = m + log l
