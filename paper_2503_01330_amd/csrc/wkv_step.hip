@@ -619,7 +619,7 @@ void wkv_step_kernel(WkvCache c, const void* __restrict__ q_, const void* __rest
                     // V[r] <- (abar_j V[j] + abar_r V[r]) / (abar_j + abar_r)     (Algorithm 1, Section IV)
                     const double vj = (double)bits_elem<TT>(vj_b[e]);
                     const double vr = (double)bits_elem<TT>(vr_b[e]);
-                    store_elem_f64<TT>(dst, col, zero_den ? 0.5 * vj + 0.5 * vr : (sj * vj + sr * vr) / den);
+                    store_elem_f64<TT, STREAM>(dst, col, zero_den ? 0.5 * vj + 0.5 * vr : (sj * vj + sr * vr) / den);
                 }
             }
             if (lane == 0 && zero_den) atomicAdd(&c.status[0], 1);
@@ -629,8 +629,8 @@ void wkv_step_kernel(WkvCache c, const void* __restrict__ q_, const void* __rest
             for (int e = 0; e < EPW; ++e) {
                 const int col = lane + 64 * e;
                 if (col < D) {
-                    if (!(merge && r == Lc)) store_bits<TT>(Vc + (size_t)dest * ROWB, col, vnew_b[e]);
-                    store_bits<TT>(Kc + (size_t)dest * ROWB, col, knew_b[e]);
+                    if (!(merge && r == Lc)) store_bits<TT, STREAM>(Vc + (size_t)dest * ROWB, col, vnew_b[e]);
+                    store_bits<TT, STREAM>(Kc + (size_t)dest * ROWB, col, knew_b[e]);
                 }
             }
         }
@@ -650,15 +650,15 @@ void wkv_step_kernel(WkvCache c, const void* __restrict__ q_, const void* __rest
                     const double vr = (double)bits_elem<TT>(vr_b[e]);
                     const double x = zero_den ? 0.5 * vj + 0.5 * vr : (sj * vj + sr * vr) / den;
                     if (r == Lc) {
-                        store_elem_f64<TT>(Vc + (size_t)dest * ROWB, col, x);   // folded straight into the new token
+                        store_elem_f64<TT, STREAM>(Vc + (size_t)dest * ROWB, col, x);   // folded straight into the new token
                     } else {
-                        store_elem_f64<TT>(Vc + (size_t)r * ROWB, col, x);
-                        store_bits<TT>(Vc + (size_t)dest * ROWB, col, vnew_b[e]);
+                        store_elem_f64<TT, STREAM>(Vc + (size_t)r * ROWB, col, x);
+                        store_bits<TT, STREAM>(Vc + (size_t)dest * ROWB, col, vnew_b[e]);
                     }
                 } else {
-                    store_bits<TT>(Vc + (size_t)dest * ROWB, col, vnew_b[e]);
+                    store_bits<TT, STREAM>(Vc + (size_t)dest * ROWB, col, vnew_b[e]);
                 }
-                store_bits<TT>(Kc + (size_t)dest * ROWB, col, knew_b[e]);
+                store_bits<TT, STREAM>(Kc + (size_t)dest * ROWB, col, knew_b[e]);
             }
         }
         if (lane == 0 && merge && zero_den) atomicAdd(&c.status[0], 1);
@@ -677,15 +677,15 @@ void wkv_step_kernel(WkvCache c, const void* __restrict__ q_, const void* __rest
                 if (i < Lc) {
                     if (!RANK0 && !QUAD) cnt += (pos_reg[k] < pj) ? 1 : 0;   // the victim's rank in token order, for the log
                     if (i != j) {
-                        au[i] = al[i];
+                        store_state<STREAM>(&au[i], al[i]);
                         const int n = nxt_reg[k];
                         int nn = n;
                         if (n < 0) nn = dest;
                         else if (n == j) nn = (r == Lc) ? dest : r;
-                        if (nn != n) nu[i] = nn;
+                        if (nn != n) store_state<STREAM>(&nu[i], nn);
                     }
                 } else if (i == Lc) {
-                    au[dest] = al[Lc]; pu[dest] = t; nu[dest] = -1;
+                    store_state<STREAM>(&au[dest], al[Lc]); store_state<STREAM>(&pu[dest], (int32_t)t); store_state<STREAM>(&nu[dest], (int32_t)-1);
                 }
             }
         }
