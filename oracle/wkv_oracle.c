@@ -13,10 +13,12 @@
  *
  * Pins: every function below is checked in tests/test_oracle_pins.py against something
  * other than itself (numbers the paper prints, library softmax attention, closed forms,
- * invariants, a separately written list simulator).  Parity unpinned: only what no
- * implementation-free fact covers -- how close the compressed cache stays to full
- * attention (the paper's evidence is perplexity on data that is not available), and the
- * two eviction-rule variants beyond the special cases tested.  The bulk prefill
+ * invariants, a separately written token-table simulator; the eviction-rule variants at every
+ * step against an uncompressed library-attention run restricted to the survivors).  Parity
+ * unpinned: only what no implementation-free fact covers -- how close the compressed cache
+ * stays to full attention (the paper's evidence is perplexity on data that is not
+ * available).  The zero-denominator branch of the merge is a reading of a case the paper
+ * leaves undefined; the tests check that it does what the reading says, nothing more.  The bulk prefill
  * (orc_prefill) is a reading, not the paper's procedure; it is pinned to causal library
  * attention, to the streaming path where the two must coincide (P <= m + 1), to the list
  * simulator, and to the sorted-score consequence of its fixed scores.

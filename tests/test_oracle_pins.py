@@ -321,6 +321,48 @@ def test_merge_weights_are_the_two_average_scores():
     assert np.array_equal(np.delete(sf["a"], j), st["a"])
 
 
+def test_zero_denominator_is_a_reading_and_both_implementations_take_it():
+    """Both averages zero: the merge formula of Algorithm 1 is 0/0 there and the paper says nothing.
+    The reading taken (weights 1/2, 1/2) is NOT a fact the paper or the mathematics fixes; this test
+    only makes sure that the branch does what the reading says, in the C oracle and in the
+    separately written simulator alike, and that it is reached the way a real stream reaches it:
+    through scores that underflow to exactly 0 (keys that point away from every query)."""
+    # the primitive: 0, 0 -> the plain mean; anything positive -> the convex combination
+    a, b = np.array([1.0, -2.0, 8.0]), np.array([3.0, 6.0, -8.0])
+    assert np.array_equal(oracle.merge_pair(0.0, 0.0, a, b), 0.5 * a + 0.5 * b)
+    assert np.array_equal(oracle.merge_pair(0.0, 2.0, a, b), b)
+    assert np.allclose(oracle.merge_pair(1.0, 3.0, a, b), 0.25 * a + 0.75 * b, rtol=1e-15)
+    # a stream: tokens 1 and 2 carry keys opposite to every query, scaled so that their softmax
+    # weights are exp(-1e4) = 0 in fp64 at every step; everything else attends normally
+    d, m, T = 8, 5, 9
+    g = np.random.default_rng(5)
+    base = np.zeros(d); base[0] = 1.0
+    q = np.tile(base * 100.0, (T, 1, 1)).astype(np.float64)              # [T, units=1, d]
+    k = g.standard_normal((T, 1, d)) * 0.01
+    k[:, 0, 0] = np.abs(k[:, 0, 0])
+    k[1, 0] = -base * 300.0; k[2, 0] = -base * 300.0                      # logit -30000/sqrt(8) against ~0
+    v = g.standard_normal((T, 1, d))
+    q, k, v = (x.astype(np.float32) for x in (q, k, v))                  # what both sides are given
+    orc = oracle.Oracle(1, d, m, 1)
+    res = orc.run(q[:m + 1], k[:m + 1], v[:m + 1])                        # up to and including the first compression
+    # token 0 collects all the mass of step 0; tokens 1 and 2 never collect any: average 0, the lowest,
+    # ties to the oldest -> token 1 goes first and folds into token 2 with weights 1/2, 1/2
+    assert res["evict_pos"][m, 0] == 1 and res["evict_score"][m, 0] == 0.0
+    st = orc.state(0)
+    assert list(st["pos"]) == [0, 2, 3, 4, 5]
+    assert np.array_equal(st["V"][1], 0.5 * v[1, 0].astype(np.float64) + 0.5 * v[2, 0].astype(np.float64))
+    assert st["a"][1] == 0.0                                              # the survivor keeps its own (zero) mass
+    res2 = orc.run(q[m + 1:], k[m + 1:], v[m + 1:])                       # token 2 goes next, the same way
+    assert res2["evict_pos"][0, 0] == 2 and res2["evict_score"][0, 0] == 0.0
+    st = orc.state(0)
+    from oracle import brute
+    sim = brute.BruteUnit(d, m, 1)
+    for t in range(T):
+        sim.step([float(x) for x in q[t, 0]], [float(x) for x in k[t, 0]], [float(x) for x in v[t, 0]])
+    assert list(sim.pos) == list(st["pos"])
+    assert np.allclose(np.array(sim.V), st["V"], rtol=1e-12, atol=1e-14)
+
+
 def test_storage_rounding_of_merged_rows():
     n, d, m = 80, 16, 6
     q, k, v = rand_stream(90, n, 1, d, np.float16)
