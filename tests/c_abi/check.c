@@ -5,13 +5,15 @@
  * vector; the cache holds min(tokens, budget) slots; token positions are strictly increasing
  * and end at the newest token; merge counts sum to the number of tokens; the eviction log
  * names tokens outside the recent window.  Then the same facts for a prompt that goes through
- * wkv_prefill into an fp16 cache, followed by one decode step.  Prints "c_abi ok" and exits 0
- * on success.
+ * wkv_prefill into an fp16 cache, followed by one decode step; the same through wkv_create_ex
+ * (device-side token index) and wkv_prefill_noalloc; wkv_launch_shape; wkv_probe_read.
+ * Prints "c_abi ok" and exits 0 on success.
  */
 #include <hip/hip_runtime_api.h>
 #include <math.h>
 #include <stdio.h>
 #include <stdlib.h>
+#include <string.h>
 
 #include "../../include/wkv.h"
 
@@ -148,6 +150,37 @@ int main(void)
             CHECK(pos[u * M + M - 1] == PT && total == PT + 1);
         }
         WKV(wkv_destroy(h));
+
+        /* ---- the same prompt through wkv_prefill_noalloc, into a handle made with wkv_create_ex whose
+         * token index lives on the device (replayable): the retained tokens must be the same */
+        {
+            wkv_options o;
+            memset(&o, 0, sizeof o);
+            o.batch = B; o.heads = H; o.head_dim = D; o.budget = M; o.recent_window = R; o.dtype = WKV_FP16;
+            o.max_prompt = PT; o.replayable = 1;
+            int groups = 0, threads = 0;
+            WKV(wkv_launch_shape(&o, &groups, &threads));
+            CHECK(groups >= UNITS && groups % UNITS == 0 && (threads == 256 || threads == 512 || threads == 1024));
+            o.reserved[0] = 1;
+            CHECK(wkv_launch_shape(&o, &groups, &threads) == WKV_EINVAL);   /* reserved fields must be zero */
+            o.reserved[0] = 0;
+            wkv_handle* h2 = NULL;
+            WKV(wkv_create_ex(&h2, &o));
+            WKV(wkv_prefill_noalloc(h2, gq, gk, gv, go, PT, NULL));
+            WKV(wkv_step(h2, gq + PT * step, gk + PT * step, gv + PT * step, go + PT * step, NULL));
+            int64_t tokens2 = 0;
+            int32_t pos2[UNITS * M];
+            WKV(wkv_state(h2, WKV_STEP, &tokens2, sizeof tokens2));
+            WKV(wkv_state(h2, WKV_POS, pos2, sizeof pos2));
+            CHECK(tokens2 == PT + 1);
+            CHECK(memcmp(pos2, pos, sizeof pos2) == 0);
+            WKV(wkv_destroy(h2));
+        }
+        /* ---- the streaming-read yardstick: argument checks and one launch */
+        CHECK(wkv_probe_read(NULL, 4096, 4, 256, 0, NULL, NULL) == WKV_EINVAL);
+        CHECK(wkv_probe_read(gq, 4096 + 16, 4, 256, 0, NULL, NULL) == WKV_EINVAL);
+        WKV(wkv_probe_read(gq, (np * 2) / 64 * 64, 4, 256, 1, NULL, NULL));
+        HIP(hipDeviceSynchronize());
         HIP(hipFree(gq)); HIP(hipFree(gk)); HIP(hipFree(gv)); HIP(hipFree(go));
         free(pq); free(pk); free(pv); free(po);
     }
