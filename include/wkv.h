@@ -248,8 +248,10 @@ int wkv_launch_shape(const wkv_options* opt, int* workgroups, int* threads);
  * Measurement aid, no part of the method: a plain streaming read of `bytes` bytes of DEVICE memory
  * at `src` by `workgroups` workgroups of `threads` threads (64..1024, a multiple of 64), each
  * workgroup its own contiguous share, 16 bytes per lane and load, four loads in flight per lane;
- * non-temporal loads if `nontemporal` is non-zero.  Nothing is written (`sink`, 4 bytes of device
- * memory or NULL, only keeps the loads alive).  Asynchronous on `stream`.  The benchmark times it
+ * non-temporal loads if `nontemporal` is non-zero.  `sink` (4 bytes of device memory, or NULL)
+ * keeps the loads alive: a lane whose loaded words XOR to 0x9E3779B9 stores that constant there --
+ * with ordinary data practically never, and a test that plants the constant in one word of an
+ * otherwise zero buffer sees that the word was read.  Asynchronous on `stream`.  The benchmark times it
  * with the grid and byte count of a wkv_step launch: what that launch shape can pull out of
  * memory when it does nothing else.  `bytes` must be a positive multiple of 16*workgroups
  * (WKV_EINVAL otherwise); the caller owns src and keeps it valid.
