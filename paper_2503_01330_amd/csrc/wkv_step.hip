@@ -586,6 +586,12 @@ void wkv_step_kernel(WkvCache c, const void* __restrict__ q_, const void* __rest
         }
     }
     WKV_MARK(4);
+    if constexpr (QUAD) {
+        // The rows a bookkeeping wave fetched for its candidate include the victim's, whose slot wave 0
+        // overwrites with the incoming token right after the barrier: those loads have to be complete,
+        // in every bookkeeping wave, before anybody passes it.  They were issued a microsecond ago.
+        if (wid < NBK) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    }
     WKV_LDS_BARRIER();   // barrier 2: victim and neighbour are known, per-wave partials are staged
     WKV_MARK(5);
 
