@@ -13,7 +13,10 @@ What the line carries:
   roofline              algorithmic bytes per launch / average launch duration (HIP events around
                         the same regions) against the 8 TB/s HBM peak -- and against what a plain
                         streaming read with the same grid and byte count reaches in this run
-                        (achievable_peak, frac_of_achievable), measured through wkv_probe_read;
+                        (achievable_peak, frac_of_achievable), measured through wkv_probe_read; next to it
+                        what the stack would take if its launches could overlap at their ends
+                        (layers_unordered: two streams in turn; no valid order for layers that feed each
+                        other, a yardstick for the cost of the launch boundaries);
   also                  the other configurations (cfg2, cfg4, cfg5), each with its own roofline;
                         cache_resident marks those whose whole K and V fit the 256 MB last-level
                         cache, whose fraction is therefore no HBM figure; for those, as_stack is the
@@ -115,7 +118,7 @@ def main():
         cfg = synth.CONFIGS[name]
         layers = layers or cfg.layers
         fill = cfg.budget                       # tokens streamed (untimed) until the cache is full
-        total = fill + W + REPS * K
+        total = fill + W + (REPS + 1) * K     # (+1: the two-stream yardstick below)
         cfg = synth.scaled(cfg, steps=total, layers=max(layers, cfg.layers))
         code = synth.DTYPE_CODE[cfg.dtype]
         eb = synth.DTYPE_BYTES[cfg.dtype]
@@ -157,6 +160,27 @@ def main():
             torch.cuda.synchronize()
             walls.append(time.perf_counter() - w0)
             evs.append(ev0.elapsed_time(ev1))
+        # What the launch boundaries cost: the same steps once more, the handles of the stack taken from two
+        # streams in turn, so that a launch starts on compute units as the one before leaves them.  No valid
+        # order for a model (a layer's q, k, v follow from the layer before; here they are staged
+        # inputs, and every handle keeps its own stream, so the results are the same): a yardstick only.
+        unordered_us = None
+        if layers >= 2 and layers % 2 == 0 and not args.skip_probe:
+            side = torch.cuda.Stream()
+            main = torch.cuda.current_stream()
+            side.wait_stream(main)
+            two = (main.cuda_stream, side.cuda_stream)
+            lo = fill + W + REPS * K
+            ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            ev0.record()
+            for t in range(lo, lo + K):
+                off = t * stride
+                for i, (h, (pq, pk, pv, po)) in enumerate(zip(handles, ptrs)):
+                    step(h, pq + off, pk + off, pv + off, po + off, two[i & 1])
+            main.wait_stream(side)
+            ev1.record()
+            torch.cuda.synchronize()
+            unordered_us = ev0.elapsed_time(ev1) * 1e3 / (K * layers)
         step_bytes = caches[0].step_bytes()              # algorithmic bytes of one launch
         # which kernel the library launches for this shape: the sliced one allocates scratch
         o = caches[0].opt
@@ -172,7 +196,7 @@ def main():
         kv_bytes = 2 * layers * cfg.units * (cfg.budget + 1) * cfg.head_dim * eb
         return dict(cfg=cfg, layers=layers, fill=fill, wall=wall, walls=walls, gen_s=gen_s, step_bytes=step_bytes,
                     kernel=kernel, kernel_us=kernel_us, achieved=step_bytes / (kernel_us * 1e-6) / 1e9,
-                    tokens_per_s=cfg.batch * K / wall, grid=grid, kv_bytes=kv_bytes,
+                    tokens_per_s=cfg.batch * K / wall, grid=grid, kv_bytes=kv_bytes, unordered_us=unordered_us,
                     ev_us=[e * 1e3 / (K * layers) for e in evs])
 
     def probe(mm):
@@ -189,6 +213,7 @@ def main():
         stream = torch.cuda.current_stream().cuda_stream
         launches = max(K * mm["layers"], 64)
         res = {}
+
         for label, nt in (("cached", False), ("nontemporal", True)):
             times = []
             for r in range(REPS + 1):
@@ -218,6 +243,12 @@ def main():
             best = max(pr["cached"]["GB/s"], pr["nontemporal"]["GB/s"])
             r["achievable_peak"] = best
             r["frac_of_achievable"] = round(mm["achieved"] / best, 4)
+            if mm["unordered_us"] is not None:
+                r["layers_unordered"] = {"us_per_launch": round(mm["unordered_us"], 3),
+                                         "frac": round(mm["step_bytes"] / (mm["unordered_us"] * 1e-6) / 1e9 / HBM_PEAK_GBS, 4),
+                                         "what": "the same steps with the stack's handles taken from two streams in turn, "
+                                                 "so that launches overlap at their ends; not a valid order for layers that "
+                                                 "feed each other: what the launch boundaries cost"}
             r["streaming_read"] = {"bytes_per_launch": nbytes, **pr,
                                    "what": "wkv_probe_read: same grid, same bytes per launch, same number of rotating "
                                            "buffers as layers; reads only"}
