@@ -167,9 +167,9 @@ def main():
         unordered_us = None
         if layers >= 2 and layers % 2 == 0 and not args.skip_probe:
             side = torch.cuda.Stream()
-            main = torch.cuda.current_stream()
-            side.wait_stream(main)
-            two = (main.cuda_stream, side.cuda_stream)
+            first = torch.cuda.current_stream()
+            side.wait_stream(first)
+            two = (first.cuda_stream, side.cuda_stream)
             lo = fill + W + REPS * K
             ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             ev0.record()
@@ -177,7 +177,7 @@ def main():
                 off = t * stride
                 for i, (h, (pq, pk, pv, po)) in enumerate(zip(handles, ptrs)):
                     step(h, pq + off, pk + off, pv + off, po + off, two[i & 1])
-            main.wait_stream(side)
+            first.wait_stream(side)
             ev1.record()
             torch.cuda.synchronize()
             unordered_us = ev0.elapsed_time(ev1) * 1e3 / (K * layers)
@@ -213,7 +213,6 @@ def main():
         stream = torch.cuda.current_stream().cuda_stream
         launches = max(K * mm["layers"], 64)
         res = {}
-
         for label, nt in (("cached", False), ("nontemporal", True)):
             times = []
             for r in range(REPS + 1):
