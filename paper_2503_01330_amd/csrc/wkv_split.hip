@@ -102,18 +102,32 @@ void wkv_split_kernel(WkvCache c, WkvSplit sp, const void* __restrict__ q_, cons
     auto row_base = [&](int r) { return lo + r * RB + (r < nfull ? gid : wid * BR + g4); };
     auto row_stride = [&](int r) { return r < nfull ? NG : 4; };
     uint32_t kw[U][NW32], vw[U][NW32];
-    auto request = [&](uint32_t (&dst)[U][NW32], const char* cached, const char* incoming, int r) {
+    // all addresses of a round first, then its loads back to back (see wkv_step.hip)
+    auto row_ptrs = [&](const char* (&rp)[U], const char* cached, const char* incoming, int r) {
         const int base = row_base(r), stride = row_stride(r);
         const int dup = (base < hi) ? base : 0;            // entry 0 always has an address (slot 0, or the incoming row)
 #pragma unroll
         for (int uu = 0; uu < U; ++uu) {
             int i = base + uu * stride;
             if (i >= hi) i = dup;
-            const char* rp = (i == Lc) ? incoming : cached + (size_t)i * ROWB;
-            load_words<NW32, STREAM>(rp + sub * LANEB, dst[uu]);
+            rp[uu] = ((i == Lc) ? incoming : cached + (size_t)i * ROWB) + sub * LANEB;
         }
     };
+    auto issue = [&](uint32_t (&dst)[U][NW32], const char* const (&rp)[U]) {
+#pragma unroll
+        for (int uu = 0; uu < U; ++uu) load_words<NW32, STREAM>(rp[uu], dst[uu]);
+    };
+    auto request = [&](uint32_t (&dst)[U][NW32], const char* cached, const char* incoming, int r) {
+        const char* rp[U];
+        row_ptrs(rp, cached, incoming, r);
+        issue(dst, rp);
+    };
     request(kw, Kc, ku, 0);
+    // where the first round of V rows lies: worked out now, while the K rows are on their way, so that
+    // the V requests go out the moment the last K row is used (the address arithmetic of eight rows is
+    // some hundred instructions, a third of a microsecond with two waves on a SIMD)
+    const char* vp0[U];
+    row_ptrs(vp0, Vc, vu, 0);
 
     double qd[EPL];
     {
@@ -147,7 +161,7 @@ void wkv_split_kernel(WkvCache c, WkvSplit sp, const void* __restrict__ q_, cons
         for (; r + 1 < nrounds; ++r) { logits(r); request(kw, Kc, ku, r + 1); }
         if (r < nrounds) logits(r);
     }
-    request(vw, Vc, vu, 0);
+    issue(vw, vp0);
 
     mx = fmax(fmax(readlane_f64(mx, 0), readlane_f64(mx, 16)), fmax(readlane_f64(mx, 32), readlane_f64(mx, 48)));
     if (lane == 0) wmax[wid] = mx;
@@ -211,7 +225,7 @@ void wkv_split_kernel(WkvCache c, WkvSplit sp, const void* __restrict__ q_, cons
         for (int w = 0; w < NW; ++w) num += part[w * D + tid];
         store_agent(&pou[s * D + tid], num);
     }
-    if (tid == 0) {
+    if (tid == 64) {                                       // (a workgroup has at least four waves)
         S den = (S)0;
         double es = 0.0;
         for (int w = 0; w < NW; ++w) { den += plw[w]; es += wsum[w]; }
@@ -242,20 +256,31 @@ void wkv_split_kernel(WkvCache c, WkvSplit sp, const void* __restrict__ q_, cons
     // it (score sum, token index, link).  Only the finishing workgroup reads these.
     double a_reg[MAXPT];
     int pos_reg[MAXPT], nxt_reg[MAXPT];
+    // (rounds that hold no entry and slices that do not exist are left out -- uniform conditions --:
+    //  every load instruction of 512 threads occupies the memory pipeline for a dozen cycles or more,
+    //  and four rounds of four loads plus sixteen partial rows were a microsecond of issue alone)
 #pragma unroll
     for (int k = 0; k < MAXPT; ++k) {
-        const int i = tid + k * NT;
-        const int ic = (i < Lc) ? i : 0;
-        e_reg[k] = load_agent(&lgu[(i < L) ? i : 0]);
-        a_reg[k] = au[ic];
-        pos_reg[k] = pu[ic];
-        nxt_reg[k] = nu[ic];
+        e_reg[k] = 0.0; a_reg[k] = 0.0; pos_reg[k] = 0; nxt_reg[k] = -1;
+        if (k * NT < L) {
+            const int i = tid + k * NT;
+            const int ic = (i < Lc) ? i : 0;
+            e_reg[k] = load_agent(&lgu[(i < L) ? i : 0]);
+            a_reg[k] = au[ic];
+            pos_reg[k] = pu[ic];
+            nxt_reg[k] = nu[ic];
+        }
     }
-    // ... and the partial output rows, requested now so that they arrive while the scores are ranked
+    // ... and the partial output rows, by the waves that will form o_t (the last ones: they own the
+    // fewest entries), requested now so that they arrive with the rest
+    const bool o_wave = tid >= NT - D;                     // uniform per wave
+    const int ocol = o_wave ? tid - (NT - D) : 0;
     S po_reg[16];
 #pragma unroll
-    for (int w = 0; w < 16; ++w)
-        po_reg[w] = load_agent(&pou[((w < NS) ? w : 0) * D + ((tid < D) ? tid : 0)]);
+    for (int w = 0; w < 16; ++w) {
+        po_reg[w] = (S)0;
+        if (o_wave && w < NS) po_reg[w] = load_agent(&pou[w * D + ocol]);
+    }
     // softmax over the whole row: lane w of the first wave takes slice w; global maximum, factor
     // exp(slice maximum - maximum), denominator; wmax[w] := factor / denominator, so that
     // A_t[i] = e_i * wmax[slice of i]
@@ -272,6 +297,23 @@ void wkv_split_kernel(WkvCache c, WkvSplit sp, const void* __restrict__ q_, cons
         if (lane == 0) { misc[1] = 0; misc[2] = 0; }
     }
     __syncthreads();
+
+    if (o_wave) {   // o_t = A_t^T V_t from the S partial sums                  (Section III-A)
+        // here and not at the end: it needs the softmax factors only, not the victim, and its store
+        // is acknowledged while the scores are still being ranked
+        S num = (S)0, dn = (S)0;
+#pragma unroll
+        for (int w = 0; w < 16; ++w) {
+            if (w < NS) {                                  // the common 1/denominator cancels
+                const S f = (S)wmax[w];
+                num += f * po_reg[w];
+                dn += f * (S)wsum[w];
+            }
+        }
+        const S o = num / dn;
+        if constexpr (TT::BYTES == 4) reinterpret_cast<float*>(out_)[(size_t)u * D + ocol] = (float)o;
+        else store_elem<TT>(out_, (size_t)u * D + ocol, (float)o);
+    }
 
     // a = [a, 0] + A_t; abar = a / n; candidates                           (Algorithm 1)
     Best best = { INFINITY, NONE_POS, -1 };
@@ -334,19 +376,6 @@ void wkv_split_kernel(WkvCache c, WkvSplit sp, const void* __restrict__ q_, cons
         vr_b = load_bits<TT>((r == Lc) ? vu : Vc + (size_t)r * ROWB, colc);
     }
     const uint32_t vnew = load_bits<TT>(vu, colc), knew = load_bits<TT>(ku, colc);
-
-    if (tid < D) {   // o_t = A_t^T V_t from the S partial sums                  (Section III-A)
-        S num = (S)0, dn = (S)0;
-#pragma unroll
-        for (int w = 0; w < 16; ++w) {
-            const S f = (w < NS) ? (S)wmax[w] : (S)0;      // the common 1/denominator cancels
-            num += f * po_reg[w];
-            dn += f * (S)wsum[w];
-        }
-        const S o = num / dn;
-        if constexpr (TT::BYTES == 4) reinterpret_cast<float*>(out_)[(size_t)u * D + tid] = (float)o;
-        else store_elem<TT>(out_, (size_t)u * D + tid, (float)o);
-    }
 
     if (sane) {
         // score sums, token indices, links: every entry's owner stores its own (see wkv_step.hip)
