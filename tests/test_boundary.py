@@ -99,3 +99,11 @@ def test_launch_shape_follows_the_unit_count():
     assert shape(8, 32, 410, threads=512, split=2) == (512, 512)
     with pytest.raises(wkv.WkvError):
         shape(8, 32, 410, threads=300)
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """bench.py measures exactly one GPU: a larger --gpus exits with a message before anything is imported."""
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert r.returncode == 2 and "one GPU" in r.stderr and r.stdout.strip() == ""
